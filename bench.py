@@ -110,7 +110,7 @@ def run_network(a):
         px_in, px_out = N * l.H * l.W, N * l.Ho * l.Wo
         alg_bytes += 2 * (px_in * l.C + px_out * l.M)
         if l.kind == "gdws":
-            G = int(workloads.configs.draw_g(l).sum())
+            G = int(workloads.configs.draw_g(l, gd.gdws_budget_gamma).sum())
             flops += 2.0 * px_out * G * (l.K * l.K + l.M)
             alg_bytes += 2 * G * (l.K * l.K + l.M)
         elif l.kind == "dense":
@@ -152,7 +152,7 @@ def main():
     dtype, b = "bf16", 2
     if a.workload == "config2":
         s, r = gd.gdws_singular_values(c2["Wt"])
-        g = gd.gdws_mego(s, r, c2["gamma"], g_init=np.ones(C, np.int32), cap=9)
+        g = gd.gdws_mego(s, r, gd.gdws_budget_gamma(c2["rho"], C, K, M), g_init=np.ones(C, np.int32), cap=9)
     else:
         g = np.full(C, 9 if a.workload == "config2_g9" else 1, np.int32)
     G = int(g.sum())

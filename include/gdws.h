@@ -43,7 +43,8 @@ typedef enum {
     GDWS_ENULL = -2,        /* a required pointer is NULL */
     GDWS_EUNSUPPORTED = -3, /* valid request this build has no kernel for */
     GDWS_EWORKSPACE = -4,   /* workspace missing or too small */
-    GDWS_EHIP = -5          /* the HIP runtime reported an error */
+    GDWS_EHIP = -5,         /* the HIP runtime reported an error */
+    GDWS_ENOMEM = -6        /* a host allocation failed */
 } gdws_status_t;
 
 typedef enum { GDWS_F32 = 0, GDWS_F16 = 1, GDWS_BF16 = 2 } gdws_dtype_t;
@@ -81,11 +82,33 @@ int gdws_singular_values(const float *W, int32_t M, int32_t C, int32_t K, double
 int gdws_mego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, const double *alpha,
               int64_t gamma, int32_t cap, int32_t *g);
 
-/* Algorithm 2 (LEGO): least-complex g with weighted error <= beta, following
- * Theorem 2 (filters are dropped, smallest alpha*sigma^2 first, while the sum of
- * dropped terms stays <= beta^2).  g host [C] out; no channel goes below g_min. */
+/* Algorithm 2 (LEGO): least-complex g with weighted error <= beta.  Filters are
+ * dropped, smallest alpha*sigma^2 first, while the bound holds.  compare selects
+ * the reading of the bound: GDWS_LEGO_THEOREM follows Theorem 2 and its proof (the
+ * sum of dropped squared terms stays <= beta^2); GDWS_LEGO_LISTING takes the
+ * algorithm box literally (the running sum is compared with beta itself, strictly)
+ * -- the paper's two statements differ and no printed value decides between them.
+ * g host [C] out; no channel goes below g_min. */
+typedef enum { GDWS_LEGO_THEOREM = 0, GDWS_LEGO_LISTING = 1 } gdws_lego_compare_t;
 int gdws_lego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, const double *alpha,
-              double beta, int32_t g_min, int32_t *g);
+              double beta, int32_t g_min, int32_t compare, int32_t *g);
+
+/* Total multiplier budget for a complexity target (eq. 3 against eq. 2): the
+ * largest G with G (K^2 + M) <= rho * C K^2 M, kept within [C, min(K^2, M) * C].
+ * This is the gamma handed to gdws_mego when every layer is cut to the same
+ * fraction rho of its MACs (Section 4.4, the GDWS-U setting).  Negative
+ * gdws_status_t on invalid arguments. */
+int64_t gdws_budget_gamma(double rho, int32_t C, int32_t K, int32_t M);
+
+/* Sparse-aware reduction (Appendix B): intermediate channels whose depthwise
+ * filter is all zero, or whose pointwise column is all zero, contribute nothing
+ * and are removed.  For a pruned W this turns any g >= rank into g_c = rank(W_c).
+ * g host [C], dw host [G][K][K], pw host [M][G] in; g_out host [C]; dw_out
+ * [G'][K][K], pw_out [M][G'], keep [G'] (index in the original of each kept
+ * channel) may be NULL and need room for G entries.  Returns G' >= 0, or a
+ * negative gdws_status_t. */
+int gdws_compact_factors(int32_t C, int32_t M, int32_t K, const int32_t *g, const float *dw,
+                         const float *pw, int32_t *g_out, float *dw_out, float *pw_out, int32_t *keep);
 
 /* Build a layer plan.  g host [C], g[c] >= 0, sum(g) >= 1.  Exactly one of
  *   W  host [M][C][K][K]: the library factorises each W_c by truncated SVD of
@@ -95,6 +118,12 @@ int gdws_lego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, co
  * desc->dtype; bias stays fp32. */
 int gdws_plan(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, const float *dw,
               const float *pw, const float *bias, gdws_plan_t **out);
+/* gdws_plan followed by the sparse-aware reduction of Appendix B on the rounded
+ * factors: the plan's tables (gdws_plan_info) and factors (gdws_plan_factors) are
+ * those of the reduced vector g' <= g, and the forward pass does G' (K^2 + M) MACs
+ * per pixel.  GDWS_EINVAL if nothing is left. */
+int gdws_plan_sparse(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, const float *dw,
+                     const float *pw, const float *bias, gdws_plan_t **out);
 int gdws_plan_destroy(gdws_plan_t *plan);
 
 /* Tables of a plan (Property 2).  Any output pointer may be NULL.  offsets
@@ -131,7 +160,9 @@ int gdws_forward(const gdws_plan_t *plan, const void *x, const void *residual, v
  * x dev [N,H,W,C]; y dev [N,H'/2,W'/2,M] (floor).  Only where the matrix-core
  * fused kernel applies (NHWC, 16-bit storage, K = 3, pad = 1, M % 8 == 0, no
  * residual): otherwise GDWS_EUNSUPPORTED and nothing is launched -- the caller
- * then runs gdws_forward and a pooling pass.  GDWS_EINVAL if H' or W' < 2. */
+ * then runs gdws_forward and a pooling pass.  GDWS_EINVAL if H' or W' < 2, or if
+ * x and y overlap in memory (tiles of y are stored while other tiles of x are
+ * still being read). */
 int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32_t N, int32_t H,
                           int32_t W, void *stream);
 
@@ -184,7 +215,9 @@ int gdws_net_create(const gdws_net_layer_t *layers, int32_t n_layers, gdws_net_t
 int gdws_net_destroy(gdws_net_t *net);
 
 /* Bytes of device workspace for a batch of N inputs of H x W (activation buffers
- * of every node whose output is still needed, plus per-layer scratch). */
+ * of every node whose output is still needed, plus per-layer scratch).  The
+ * buffer assignment for (N, H, W) is worked out here, once, and kept in the
+ * network object (host memory); gdws_network_forward reuses it. */
 size_t gdws_net_workspace_bytes(const gdws_net_t *net, int32_t N, int32_t H, int32_t W);
 
 /* Runs every node in order on `stream`; y receives the last node's output. */

@@ -254,6 +254,36 @@ def lego(S, beta, alpha=None, compare="beta_squared", g_min=0, dim=None):
     return g
 
 
+def sparse_g(W):
+    """g_c = rank(W_c): the smallest g whose GDWS convolution reproduces a (pruned) W with no error.
+
+    Appendix B: very sparse weight matrices have low-rank sub-matrices W_c, and by Lemma 1 a
+    GDWS convolution with g_c = rank(W_c) is exact.
+    """
+    _, S, _ = svd_slices(W)
+    M, _, K, _ = np.shape(W)
+    return np.array([numerical_rank(S[c], max(M, K * K)) for c in range(S.shape[0])], dtype=np.int32)
+
+
+def compact_factors(g, D, Pw):
+    """Drop the intermediate channels that cannot contribute (Appendix B: the factors of a pruned W are sparse too).
+
+    Channel j is dead if its depthwise filter D[j] is all zero (its map is zero) or its pointwise
+    column Pw[:, j] is all zero (its map is never read).  Returns (g', D', Pw', keep) with keep[q] the
+    index in the original of kept channel q; g'_c counts the kept channels of input channel c.
+    """
+    D, Pw = _f64(D), _f64(Pw)
+    h = offsets(g)
+    keep, g2 = [], np.zeros(len(g), dtype=np.int32)
+    for c in range(len(g)):
+        for j in range(h[c], h[c + 1]):
+            if np.any(D[j] != 0.0) and np.any(Pw[:, j] != 0.0):
+                keep.append(j)
+                g2[c] += 1
+    keep = np.asarray(keep, dtype=np.int32)
+    return g2, D[keep], Pw[:, keep], keep
+
+
 def gamma_from_budget(rho, C, K, M):
     """Largest G with G (K^2 + M) <= rho * C K^2 M (eq. 3 against eq. 2), kept within [C, min(K^2, M) C]."""
     gam = int(np.floor(rho * C * K * K * M / (K * K + M) + 1e-9))

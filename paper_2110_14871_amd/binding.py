@@ -10,7 +10,7 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("GDWS_LIBRARY", os.path.join(_PKG, "libgdws.so"))   # override: an alternate build
+LIB_PATH = os.path.join(_PKG, "libgdws.so")
 
 F32, F16, BF16 = 0, 1, 2
 NCHW, NHWC = 0, 1
@@ -51,7 +51,10 @@ def lib():
             "gdws_strerror": (ctypes.c_char_p, [ctypes.c_int]),
             "gdws_singular_values": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
             "gdws_mego": (ctypes.c_int, [vp, vp, i32, i32, vp, i64, i32, vp]),
-            "gdws_lego": (ctypes.c_int, [vp, vp, i32, i32, vp, dbl, i32, vp]),
+            "gdws_lego": (ctypes.c_int, [vp, vp, i32, i32, vp, dbl, i32, i32, vp]),
+            "gdws_budget_gamma": (i64, [dbl, i32, i32, i32]),
+            "gdws_compact_factors": (ctypes.c_int, [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]),
+            "gdws_plan_sparse": (ctypes.c_int, [pdesc, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]),
             "gdws_plan": (ctypes.c_int, [pdesc, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]),
             "gdws_plan_destroy": (ctypes.c_int, [vp]),
             "gdws_plan_info": (ctypes.c_int, [vp, ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp),
@@ -77,7 +80,8 @@ def lib():
     return _lib
 
 
-EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_mego", "gdws_lego", "gdws_plan", "gdws_plan_destroy",
+EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_mego", "gdws_lego", "gdws_budget_gamma",
+           "gdws_compact_factors", "gdws_plan_sparse", "gdws_plan", "gdws_plan_destroy",
            "gdws_plan_info", "gdws_plan_factors", "gdws_intermediate_channels", "gdws_workspace_bytes", "gdws_forward",
            "gdws_forward_maxpool2", "gdws_gdw_forward",
            "gdws_pw_forward", "conv_dense_workspace_bytes", "conv_dense_forward", "gdws_net_create",
@@ -143,14 +147,41 @@ def gdws_mego(sigma, rank, gamma, alpha=None, g_init=None, cap=0):
     return g
 
 
-def gdws_lego(sigma, rank, beta, alpha=None, g_min=0):
+LEGO_THEOREM, LEGO_LISTING = 0, 1
+
+
+def gdws_lego(sigma, rank, beta, alpha=None, g_min=0, compare=LEGO_THEOREM):
     sk, sp = _host(sigma, np.float64)
     rk, rp = _host(rank, np.int32)
     ak, ap = _host(alpha, np.float64)
     C, R = sk.shape
     g = np.zeros(C, dtype=np.int32)
-    _check(lib().gdws_lego(sp, rp, C, R, ap, float(beta), int(g_min), g.ctypes.data_as(ctypes.c_void_p)), "gdws_lego")
+    _check(lib().gdws_lego(sp, rp, C, R, ap, float(beta), int(g_min), int(compare),
+                           g.ctypes.data_as(ctypes.c_void_p)), "gdws_lego")
     return g
+
+
+def gdws_budget_gamma(rho, C, K, M):
+    v = int(lib().gdws_budget_gamma(float(rho), C, K, M))
+    _check(min(v, 0), "gdws_budget_gamma")
+    return v
+
+
+def gdws_compact_factors(g, dw, pw):
+    """(g' int32 [C], dw' [G', K, K], pw' [M, G'], keep int32 [G']): the factors without their dead channels."""
+    gk, gp = _host(g, np.int32)
+    dk, dp = _host(dw, np.float32)
+    pk, pp = _host(pw, np.float32)
+    G, K = dk.shape[0], dk.shape[1]
+    M = pk.shape[0]
+    if pk.shape[1] != G or int(gk.sum()) != G:
+        raise ValueError("g, dw [G, K, K] and pw [M, G] do not agree")
+    g_out = np.zeros(len(gk), np.int32)
+    dw_out, pw_out, keep = np.zeros((G, K, K), np.float32), np.zeros(M * G, np.float32), np.zeros(G, np.int32)
+    vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    n = lib().gdws_compact_factors(len(gk), M, K, gp, dp, pp, vp(g_out), vp(dw_out), vp(pw_out), vp(keep))
+    _check(min(n, 0), "gdws_compact_factors")
+    return g_out, dw_out[:n].copy(), pw_out[:M * n].reshape(M, n).copy(), keep[:n].copy()
 
 
 class Plan:
@@ -171,7 +202,8 @@ class Plan:
             pass
 
 
-def gdws_plan(desc, g, W=None, dw=None, pw=None, bias=None):
+def gdws_plan(desc, g, W=None, dw=None, pw=None, bias=None, sparse=False):
+    """sparse=True: gdws_plan_sparse (dead intermediate channels are dropped at plan time)."""
     gk, gp = _host(g, np.int32)
     if len(gk) != desc.C:
         raise ValueError("g must have C entries")
@@ -189,7 +221,8 @@ def gdws_plan(desc, g, W=None, dw=None, pw=None, bias=None):
     if bk is not None and bk.size != desc.M:
         raise ValueError("bias must be [M]")
     h = ctypes.c_void_p()
-    _check(lib().gdws_plan(ctypes.byref(desc), gp, wp, dp, pp, bp, ctypes.byref(h)), "gdws_plan")
+    fn = lib().gdws_plan_sparse if sparse else lib().gdws_plan
+    _check(fn(ctypes.byref(desc), gp, wp, dp, pp, bp, ctypes.byref(h)), "gdws_plan_sparse" if sparse else "gdws_plan")
     return Plan(h, desc)
 
 

@@ -2,6 +2,8 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -10,6 +12,13 @@
 #include "planner.h"
 
 using namespace gdws;
+
+// No exception crosses the C boundary: host allocation failures inside an entry point become a status.
+#define GDWS_TRY try {
+#define GDWS_CATCH                                   \
+    }                                                \
+    catch (const std::bad_alloc &) { return GDWS_ENOMEM; } \
+    catch (...) { return GDWS_EHIP; }
 
 // ---------------------------------------------------------------------------------
 // objects
@@ -54,11 +63,29 @@ struct NetNode {
     DenseMfmaTables dm;      // dense with 3 input channels, 16-bit NHWC: the implicit-GEMM kernel
 };
 
+struct NodeShape {
+    int C, H, W;      // output channels / size
+    size_t bytes;     // of the output tensor
+    size_t scratch;   // per-layer scratch
+    size_t offset;    // of the output buffer inside the workspace (SIZE_MAX = writes to y)
+};
+
+// Buffer assignment of a network for one input size.
+struct NetLayout {
+    int N = 0, H = 0, W = 0;
+    std::vector<NodeShape> sh;
+    size_t act_top = 0;  // end of the activation buffers = start of the per-layer scratch
+    size_t total = 0;
+};
+
 }  // namespace
 
 struct gdws_net_s {
     std::vector<NetNode> nodes;
     int dtype = 0, layout = 0;
+    // layouts worked out so far, one per input size seen (append-only, guarded by mu; entries are never moved)
+    mutable std::mutex mu;
+    mutable std::vector<std::unique_ptr<NetLayout>> layouts;
     ~gdws_net_s()
     {
         for (auto &n : nodes) {
@@ -120,6 +147,12 @@ int upload_as_dtype(void **dst, const float *src, size_t count, int dtype)
     GDWS_HIP_CHECK(hipMalloc(dst, count * 2));
     GDWS_HIP_CHECK(hipMemcpy(*dst, tmp.data(), count * 2, hipMemcpyHostToDevice));
     return GDWS_OK;
+}
+
+bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    const char *pa = (const char *)a, *pb = (const char *)b;
+    return pa < pb + nb && pb < pa + na;
 }
 
 Epilogue plan_epilogue(const gdws_plan_t *p, const void *residual)
@@ -234,12 +267,14 @@ const char *gdws_strerror(int code)
         case GDWS_EUNSUPPORTED: return "unsupported configuration";
         case GDWS_EWORKSPACE: return "workspace missing or too small";
         case GDWS_EHIP: return "HIP runtime error";
+        case GDWS_ENOMEM: return "host memory allocation failed";
         default: return "unknown status";
     }
 }
 
 int gdws_singular_values(const float *W, int32_t M, int32_t C, int32_t K, double *sigma, int32_t *rank)
 {
+    GDWS_TRY
     if (!W || !sigma) return GDWS_ENULL;
     if (M < 1 || C < 1 || K < 1) return GDWS_EINVAL;
     const int KK = K * K, R = std::min(M, KK);
@@ -252,6 +287,7 @@ int gdws_singular_values(const float *W, int32_t M, int32_t C, int32_t K, double
         if (rank) rank[c] = svd.rank;
     }
     return GDWS_OK;
+    GDWS_CATCH
 }
 
 int gdws_mego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, const double *alpha, int64_t gamma,
@@ -266,19 +302,50 @@ int gdws_mego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, co
 }
 
 int gdws_lego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, const double *alpha, double beta,
-              int32_t g_min, int32_t *g)
+              int32_t g_min, int32_t compare, int32_t *g)
 {
     if (!sigma || !rank || !g) return GDWS_ENULL;
     if (C < 1 || R < 1 || !(beta >= 0) || g_min < 0) return GDWS_EINVAL;
+    if (compare != GDWS_LEGO_THEOREM && compare != GDWS_LEGO_LISTING) return GDWS_EINVAL;
     for (int c = 0; c < C; ++c)
         if (alpha && !(alpha[c] > 0)) return GDWS_EINVAL;
-    lego(sigma, rank, C, R, alpha, beta, g_min, g);
+    lego(sigma, rank, C, R, alpha, beta, g_min, compare == GDWS_LEGO_LISTING, g);
     return GDWS_OK;
 }
 
-int gdws_plan(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, const float *dw, const float *pw,
-              const float *bias, gdws_plan_t **out)
+int64_t gdws_budget_gamma(double rho, int32_t C, int32_t K, int32_t M)
 {
+    if (!(rho >= 0) || C < 1 || K < 1 || M < 1) return GDWS_EINVAL;
+    return budget_gamma(rho, C, K, M);
+}
+
+int gdws_compact_factors(int32_t C, int32_t M, int32_t K, const int32_t *g, const float *dw, const float *pw,
+                         int32_t *g_out, float *dw_out, float *pw_out, int32_t *keep)
+{
+    GDWS_TRY
+    if (!g || !dw || !pw || !g_out) return GDWS_ENULL;
+    if (C < 1 || M < 1 || K < 1) return GDWS_EINVAL;
+    for (int c = 0; c < C; ++c)
+        if (g[c] < 0) return GDWS_EINVAL;
+    std::vector<int32_t> go, kp;
+    std::vector<float> d, p;
+    compact_factors(C, M, K * K, g, dw, pw, go, d, p, kp);
+    std::copy(go.begin(), go.end(), g_out);
+    if (dw_out) std::copy(d.begin(), d.end(), dw_out);
+    if (pw_out) std::copy(p.begin(), p.end(), pw_out);
+    if (keep) std::copy(kp.begin(), kp.end(), keep);
+    return (int)kp.size();
+    GDWS_CATCH
+}
+
+}  // extern "C"
+
+namespace {
+
+int plan_impl(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, const float *dw, const float *pw,
+              const float *bias, bool compact, gdws_plan_t **out)
+{
+    GDWS_TRY
     if (!out || !g) return GDWS_ENULL;
     int rc = check_desc(desc);
     if (rc) return rc;
@@ -295,8 +362,8 @@ int gdws_plan(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, c
     }
     if (G < 1 || G > (1 << 24)) return GDWS_EINVAL;
 
-    gdws_plan_t *p = new (std::nothrow) gdws_plan_t;
-    if (!p) return GDWS_EHIP;
+    std::unique_ptr<gdws_plan_t> holder(new gdws_plan_t);
+    gdws_plan_t *p = holder.get();
     p->desc = *desc;
     p->G = (int)G;
     p->g.assign(g, g + C);
@@ -309,6 +376,19 @@ int gdws_plan(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, c
     }
     for (auto &v : p->dw) v = round_to_dtype(v, desc->dtype);
     for (auto &v : p->pw) v = round_to_dtype(v, desc->dtype);
+    if (compact) {
+        // Appendix B: filters past a pruned slice's rank (and any other zero filter or zero column) are dropped;
+        // the tables are those of the reduced vector g
+        std::vector<int32_t> gk, keep;
+        std::vector<float> dk, pk;
+        compact_factors(C, M, KK, g, p->dw.data(), p->pw.data(), gk, dk, pk, keep);
+        if (keep.empty()) return GDWS_EINVAL;  // the layer's output would be its bias
+        p->g = gk; p->dw = dk; p->pw = pk;
+        G = (int64_t)keep.size();
+        p->G = (int)G;
+        build_tables(p->g.data(), C, p->offsets, p->chan_of);
+        g = p->g.data();
+    }
     if (desc->has_bias) p->bias.assign(bias, bias + M);
 
     rc = upload(&p->d_chan_of, p->chan_of);
@@ -354,9 +434,26 @@ int gdws_plan(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, c
             }
         }
     }
-    if (rc) { delete p; return rc; }
-    *out = p;
+    if (rc) return rc;
+    *out = holder.release();
     return GDWS_OK;
+    GDWS_CATCH
+}
+
+}  // namespace
+
+extern "C" {
+
+int gdws_plan(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, const float *dw, const float *pw,
+              const float *bias, gdws_plan_t **out)
+{
+    return plan_impl(desc, g, W, dw, pw, bias, false, out);
+}
+
+int gdws_plan_sparse(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, const float *dw, const float *pw,
+                     const float *bias, gdws_plan_t **out)
+{
+    return plan_impl(desc, g, W, dw, pw, bias, true, out);
 }
 
 int gdws_plan_destroy(gdws_plan_t *plan)
@@ -429,6 +526,9 @@ int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32
     if (plan->desc.has_residual || plan->desc.layout != GDWS_NHWC || !fused_supported(plan, N, H, W))
         return GDWS_EUNSUPPORTED;
     if (Ho < 2 || Wo < 2) return GDWS_EINVAL;  // the pooled tensor would be empty
+    // workgroups store pooled rows while others still read x: the two tensors must not share memory
+    if (ranges_overlap(x, (size_t)N * plan->desc.C * H * W * 2, y, (size_t)N * plan->desc.M * (Ho / 2) * (Wo / 2) * 2))
+        return GDWS_EINVAL;
     return run_fused(plan, x, nullptr, y, N, H, W, Ho, Wo, (hipStream_t)stream, 1);
 }
 
@@ -487,30 +587,43 @@ int conv_dense_forward(const gdws_layer_desc_t *desc, const void *w, const float
 
 namespace {
 
-struct NodeShape {
-    int C, H, W;      // output channels / size
-    size_t bytes;     // of the output tensor
-    size_t scratch;   // per-layer scratch
-    size_t offset;    // of the output buffer inside the workspace (SIZE_MAX = writes to y)
-};
-
 const gdws_layer_desc_t &node_desc(const NetNode &n)
 {
     return n.l.kind == GDWS_LAYER_GDWS ? n.l.plan->desc : n.l.desc;
 }
 
-// Shapes and workspace offsets of every node for one input size.  Buffers are
-// handed out first-fit from a free list as soon as their last reader has run.
-int layout_buffers(const gdws_net_t *net, int N, int H, int W, std::vector<NodeShape> &sh, size_t *total)
+// True if node i + 1 is a 2 x 2 / stride-2 max-pool without padding whose input is node i, and nothing else reads
+// node i: the pair can then run as one kernel.
+bool pooled_by_next(const gdws_net_t *net, int i)
 {
     const int L = (int)net->nodes.size();
+    if (i + 1 >= L || net->nodes[i].l.kind != GDWS_LAYER_GDWS) return false;
+    const auto &q = net->nodes[i + 1].l;
+    if (q.kind != GDWS_LAYER_MAXPOOL || q.src != i || q.desc.K != 2 || q.desc.stride != 2 || q.desc.pad != 0) return false;
+    for (int k = i + 2; k < L; ++k)
+        if (net->nodes[k].l.src == i || net->nodes[k].l.residual == i) return false;
+    return true;
+}
+
+// Shapes and workspace offsets of every node for one input size.  Buffers are handed out best-fit from a free
+// list; a buffer returns to the list once the output of its last reader has been placed, so no node writes
+// into a tensor it reads.  A layer that may run as one kernel with the max-pool behind it (pooled_by_next) reads its
+// input while that kernel writes the pool's output: its inputs are therefore released only after the pool's
+// output has been placed.
+int layout_buffers(const gdws_net_t *net, int N, int H, int W, NetLayout &lay)
+{
+    const int L = (int)net->nodes.size();
+    std::vector<NodeShape> &sh = lay.sh;
     sh.assign(L, NodeShape{});
-    std::vector<int> last_use(L, -1);
+    std::vector<int> release_at(L, -1);  // node after whose output placement a node's buffer is free again
     for (int i = 0; i < L; ++i) {
         const auto &l = net->nodes[i].l;
-        if (l.src >= 0) last_use[l.src] = i;
-        if (l.residual >= 0) last_use[l.residual] = std::max(last_use[l.residual], i);
+        if (l.src >= 0) release_at[l.src] = i;
+        if (l.residual >= 0) release_at[l.residual] = std::max(release_at[l.residual], i);
     }
+    std::vector<int> last_use = release_at;
+    for (int j = 0; j < L; ++j)
+        if (release_at[j] >= 0 && pooled_by_next(net, release_at[j])) ++release_at[j];
     struct Block { size_t off, size; bool free; };
     std::vector<Block> blocks;
     std::vector<int> block_of(L, -1);
@@ -544,28 +657,82 @@ int layout_buffers(const gdws_net_t *net, int N, int H, int W, std::vector<NodeS
         blocks[pick].free = false;
         block_of[i] = pick;
         sh[i].offset = blocks[pick].off;
-        // release inputs whose last reader is this node (after choosing the output: no aliasing)
         for (int j = 0; j < i; ++j)
-            if (last_use[j] == i && block_of[j] >= 0) blocks[block_of[j]].free = true;
+            if (release_at[j] == i && block_of[j] >= 0) blocks[block_of[j]].free = true;
         if (last_use[i] < 0) blocks[pick].free = true;  // dead output
     }
-    // scratch sits after the activation buffers
-    for (auto &s : sh) (void)s;
-    *total = top + ((scratch + 255) & ~(size_t)255);
+    lay.N = N; lay.H = H; lay.W = W;
+    lay.act_top = top;                                    // scratch sits after the activation buffers
+    lay.total = top + ((scratch + 255) & ~(size_t)255);
     return GDWS_OK;
 }
 
-// True if node i + 1 is a 2 x 2 / stride-2 max-pool without padding whose input is node i, and nothing else reads
-// node i: the pair can then run as one kernel.
-bool pooled_by_next(const gdws_net_t *net, int i)
+// The layout for this input size: worked out at the first request (gdws_net_workspace_bytes, which a caller needs
+// before its first forward anyway) and kept, so that a forward call neither allocates nor plans.
+int cached_layout(const gdws_net_t *net, int N, int H, int W, const NetLayout **out)
 {
+    std::lock_guard<std::mutex> lock(net->mu);
+    for (const auto &l : net->layouts)
+        if (l->N == N && l->H == H && l->W == W) { *out = l.get(); return GDWS_OK; }
+    std::unique_ptr<NetLayout> lay(new NetLayout);
+    const int rc = layout_buffers(net, N, H, W, *lay);
+    if (rc) return rc;
+    net->layouts.push_back(std::move(lay));
+    *out = net->layouts.back().get();
+    return GDWS_OK;
+}
+
+int run_network(const gdws_net_t *net, const NetLayout &lay, const void *x, void *y, int N, int H, int W, void *workspace,
+                void *stream)
+{
+    const std::vector<NodeShape> &sh = lay.sh;
+    char *ws = (char *)workspace;
+    void *scratch = ws ? ws + lay.act_top : nullptr;
+    const size_t scratch_bytes = lay.total - lay.act_top;
     const int L = (int)net->nodes.size();
-    if (i + 1 >= L) return false;
-    const auto &q = net->nodes[i + 1].l;
-    if (q.kind != GDWS_LAYER_MAXPOOL || q.src != i || q.desc.K != 2 || q.desc.stride != 2 || q.desc.pad != 0) return false;
-    for (int k = i + 2; k < L; ++k)
-        if (net->nodes[k].l.src == i || net->nodes[k].l.residual == i) return false;
-    return true;
+    int rc = GDWS_OK;
+    for (int i = 0; i < L; ++i) {
+        const NetNode &n = net->nodes[i];
+        const void *in = n.l.src < 0 ? x : ws + sh[n.l.src].offset;
+        const int ih = n.l.src < 0 ? H : sh[n.l.src].H, iw = n.l.src < 0 ? W : sh[n.l.src].W;
+        const void *res = n.l.residual >= 0 ? ws + sh[n.l.residual].offset : nullptr;
+        void *outp = sh[i].offset == SIZE_MAX ? y : ws + sh[i].offset;
+        if (n.l.kind == GDWS_LAYER_GDWS && pooled_by_next(net, i)) {
+            // the 2 x 2 max-pool that is this layer's only reader runs in its epilogue when the kernel can
+            void *pout = sh[i + 1].offset == SIZE_MAX ? y : ws + sh[i + 1].offset;
+            rc = gdws_forward_maxpool2(n.l.plan, in, pout, N, ih, iw, stream);
+            if (rc == GDWS_OK) { ++i; continue; }
+            if (rc != GDWS_EUNSUPPORTED && rc != GDWS_EINVAL) return rc;
+            rc = gdws_forward(n.l.plan, in, res, outp, N, ih, iw, scratch, scratch_bytes, GDWS_MODE_AUTO, stream);
+        } else if (n.l.kind == GDWS_LAYER_GDWS) {
+            rc = gdws_forward(n.l.plan, in, res, outp, N, ih, iw, scratch, scratch_bytes, GDWS_MODE_AUTO, stream);
+        } else if (n.l.kind == GDWS_LAYER_DENSE && n.pwm.valid) {
+            PwMfmaArgs m;
+            m.t = in; m.y = outp; m.tables = &n.pwm; m.dtype = n.l.desc.dtype; m.M = n.l.desc.M;
+            m.ep.bias = nullptr; m.ep.residual = n.l.desc.has_residual ? res : nullptr; m.ep.relu = n.l.desc.relu;
+            m.P = (int64_t)N * sh[i].H * sh[i].W;
+            m.stride = n.l.desc.stride; m.Ho = sh[i].H; m.Wo = sh[i].W; m.H = ih; m.W = iw;
+            rc = launch_pw_mfma(m, (hipStream_t)stream);
+        } else if (n.l.kind == GDWS_LAYER_DENSE && n.dm.valid &&
+                   dense_mfma_image_supported((int64_t)N * n.l.desc.C * ih * iw)) {
+            DenseMfmaArgs m;
+            m.x = in; m.y = outp; m.tables = &n.dm; m.dtype = n.l.desc.dtype; m.relu = n.l.desc.relu;
+            m.N = N; m.C = n.l.desc.C; m.H = ih; m.W = iw; m.M = n.l.desc.M; m.K = n.l.desc.K;
+            m.stride = n.l.desc.stride; m.pad = n.l.desc.pad; m.Ho = sh[i].H; m.Wo = sh[i].W;
+            rc = launch_dense_mfma(m, (hipStream_t)stream);
+        } else if (n.l.kind == GDWS_LAYER_DENSE) {
+            rc = conv_dense_forward(&n.l.desc, n.d_w, n.d_bias, in, res, outp, N, ih, iw, scratch, scratch_bytes,
+                                    stream);
+        } else {
+            PoolArgs a;
+            a.x = in; a.y = outp; a.dtype = net->dtype; a.layout = net->layout;
+            a.N = N; a.C = n.l.desc.C; a.H = ih; a.W = iw; a.K = n.l.desc.K; a.stride = n.l.desc.stride;
+            a.pad = n.l.desc.pad; a.Ho = sh[i].H; a.Wo = sh[i].W;
+            rc = launch_maxpool(a, (hipStream_t)stream);
+        }
+        if (rc) return rc;
+    }
+    return GDWS_OK;
 }
 
 }  // namespace
@@ -574,10 +741,12 @@ extern "C" {
 
 int gdws_net_create(const gdws_net_layer_t *layers, int32_t n_layers, gdws_net_t **out)
 {
+    GDWS_TRY
     if (!layers || !out) return GDWS_ENULL;
     if (n_layers < 1) return GDWS_EINVAL;
     gdws_net_t *net = new (std::nothrow) gdws_net_t;
-    if (!net) return GDWS_EHIP;
+    if (!net) return GDWS_ENOMEM;
+    std::unique_ptr<gdws_net_t> guard(net);
     net->nodes.resize(n_layers);
     for (int i = 0; i < n_layers; ++i) {
         const gdws_net_layer_t &l = layers[i];
@@ -624,10 +793,11 @@ int gdws_net_create(const gdws_net_layer_t *layers, int32_t n_layers, gdws_net_t
                 net->nodes[i].l.bias = nullptr;
             }
         }
-        if (rc) { delete net; return rc; }
+        if (rc) return rc;
     }
-    *out = net;
+    *out = guard.release();
     return GDWS_OK;
+    GDWS_CATCH
 }
 
 int gdws_net_destroy(gdws_net_t *net)
@@ -639,70 +809,26 @@ int gdws_net_destroy(gdws_net_t *net)
 size_t gdws_net_workspace_bytes(const gdws_net_t *net, int32_t N, int32_t H, int32_t W)
 {
     if (!net) return 0;
-    std::vector<NodeShape> sh;
-    size_t total = 0;
-    if (layout_buffers(net, N, H, W, sh, &total)) return 0;
-    return total;
+    try {
+        const NetLayout *lay = nullptr;
+        if (cached_layout(net, N, H, W, &lay)) return 0;
+        return lay->total;
+    } catch (...) {
+        return 0;
+    }
 }
 
 int gdws_network_forward(const gdws_net_t *net, const void *x, void *y, int32_t N, int32_t H, int32_t W,
                          void *workspace, size_t workspace_bytes, void *stream)
 {
+    GDWS_TRY
     if (!net || !x || !y) return GDWS_ENULL;
-    std::vector<NodeShape> sh;
-    size_t total = 0;
-    int rc = layout_buffers(net, N, H, W, sh, &total);
+    const NetLayout *lay = nullptr;
+    int rc = cached_layout(net, N, H, W, &lay);
     if (rc) return rc;
-    if (total > 0 && (!workspace || workspace_bytes < total)) return GDWS_EWORKSPACE;
-    size_t act_top = 0;
-    for (auto &s : sh)
-        if (s.offset != SIZE_MAX) act_top = std::max(act_top, s.offset + ((s.bytes + 255) & ~(size_t)255));
-    char *ws = (char *)workspace;
-    void *scratch = ws ? ws + act_top : nullptr;
-    const size_t scratch_bytes = total - act_top;
-    const int L = (int)net->nodes.size();
-    for (int i = 0; i < L; ++i) {
-        const NetNode &n = net->nodes[i];
-        const void *in = n.l.src < 0 ? x : ws + sh[n.l.src].offset;
-        const int ih = n.l.src < 0 ? H : sh[n.l.src].H, iw = n.l.src < 0 ? W : sh[n.l.src].W;
-        const void *res = n.l.residual >= 0 ? ws + sh[n.l.residual].offset : nullptr;
-        void *outp = sh[i].offset == SIZE_MAX ? y : ws + sh[i].offset;
-        if (n.l.kind == GDWS_LAYER_GDWS && pooled_by_next(net, i)) {
-            // the 2 x 2 max-pool that is this layer's only reader runs in its epilogue when the kernel can
-            void *pout = sh[i + 1].offset == SIZE_MAX ? y : ws + sh[i + 1].offset;
-            rc = gdws_forward_maxpool2(n.l.plan, in, pout, N, ih, iw, stream);
-            if (rc == GDWS_OK) { ++i; continue; }
-            if (rc != GDWS_EUNSUPPORTED && rc != GDWS_EINVAL) return rc;
-            rc = gdws_forward(n.l.plan, in, res, outp, N, ih, iw, scratch, scratch_bytes, GDWS_MODE_AUTO, stream);
-        } else if (n.l.kind == GDWS_LAYER_GDWS) {
-            rc = gdws_forward(n.l.plan, in, res, outp, N, ih, iw, scratch, scratch_bytes, GDWS_MODE_AUTO, stream);
-        } else if (n.l.kind == GDWS_LAYER_DENSE && n.pwm.valid) {
-            PwMfmaArgs m;
-            m.t = in; m.y = outp; m.tables = &n.pwm; m.dtype = n.l.desc.dtype; m.M = n.l.desc.M;
-            m.ep.bias = nullptr; m.ep.residual = n.l.desc.has_residual ? res : nullptr; m.ep.relu = n.l.desc.relu;
-            m.P = (int64_t)N * sh[i].H * sh[i].W;
-            m.stride = n.l.desc.stride; m.Ho = sh[i].H; m.Wo = sh[i].W; m.H = ih; m.W = iw;
-            rc = launch_pw_mfma(m, (hipStream_t)stream);
-        } else if (n.l.kind == GDWS_LAYER_DENSE && n.dm.valid &&
-                   dense_mfma_image_supported((int64_t)N * n.l.desc.C * ih * iw)) {
-            DenseMfmaArgs m;
-            m.x = in; m.y = outp; m.tables = &n.dm; m.dtype = n.l.desc.dtype; m.relu = n.l.desc.relu;
-            m.N = N; m.C = n.l.desc.C; m.H = ih; m.W = iw; m.M = n.l.desc.M; m.K = n.l.desc.K;
-            m.stride = n.l.desc.stride; m.pad = n.l.desc.pad; m.Ho = sh[i].H; m.Wo = sh[i].W;
-            rc = launch_dense_mfma(m, (hipStream_t)stream);
-        } else if (n.l.kind == GDWS_LAYER_DENSE) {
-            rc = conv_dense_forward(&n.l.desc, n.d_w, n.d_bias, in, res, outp, N, ih, iw, scratch, scratch_bytes,
-                                    stream);
-        } else {
-            PoolArgs a;
-            a.x = in; a.y = outp; a.dtype = net->dtype; a.layout = net->layout;
-            a.N = N; a.C = n.l.desc.C; a.H = ih; a.W = iw; a.K = n.l.desc.K; a.stride = n.l.desc.stride;
-            a.pad = n.l.desc.pad; a.Ho = sh[i].H; a.Wo = sh[i].W;
-            rc = launch_maxpool(a, (hipStream_t)stream);
-        }
-        if (rc) return rc;
-    }
-    return GDWS_OK;
+    if (lay->total > 0 && (!workspace || workspace_bytes < lay->total)) return GDWS_EWORKSPACE;
+    return run_network(net, *lay, x, y, N, H, W, workspace, stream);
+    GDWS_CATCH
 }
 
 }  // extern "C"

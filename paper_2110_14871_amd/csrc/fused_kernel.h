@@ -108,25 +108,8 @@ struct FusedParams {
     int c_begin0, c_count0;  // stage 0's entry of stage_tab
     int out_off;             // depthwise-only mode: dword offset in LDS of the waves' output staging areas
     int pool, Hp, Wp;        // pool != 0 (NHWC, no residual): y is the 2 x 2 / stride-2 max-pool of the output, Hp x Wp
-#ifdef GDWS_TIMING
-    unsigned long long *stamps;  // [blocks][8 waves][32] clock samples (profiling builds only)
-#endif
 };
 
-#ifdef GDWS_TIMING
-#ifdef GDWS_WALL
-#define GDWS_CLOCK() wall_clock64()
-#else
-#define GDWS_CLOCK() __builtin_readcyclecounter()
-#endif
-#define GDWS_STAMP(slot)                                                                               \
-    do {                                                                                               \
-        if (p.stamps && (threadIdx.x & 63) == 0 && blockIdx.y == 0 && (slot) < 32)                     \
-            p.stamps[((int64_t)blockIdx.x * 8 + (threadIdx.x >> 6)) * 32 + (slot)] = GDWS_CLOCK();   \
-    } while (0)
-#else
-#define GDWS_STAMP(slot) do { } while (0)
-#endif
 
 // LDS geometry: the tile's input pixels (halo included), each holding the stage's channels.
 template <int TW, int STRIDE, bool BIG> struct Geom {
@@ -208,7 +191,6 @@ void gdws_fused_kernel(FusedParams params)
     uint16_t *tile16 = (uint16_t *)lds;
     float *tile32 = (float *)lds;
     int *pixtab = p.residual ? (int *)(tile32 + kRows * kRowFloats) : (int *)(tile16 + kRows * kRowHalfs);
-    GDWS_STAMP(0);
 
     if (SELF || threadIdx.x >= kComputeThreads) {
         // ================================ loader waves ================================
@@ -269,7 +251,6 @@ void gdws_fused_kernel(FusedParams params)
                 };
                 issue(0);
                 if (Gm::NCH > 1 && nch > 1) issue(1);
-                GDWS_STAMP(2 + 2 * (st & 1));
 #pragma unroll
                 for (int ch = 0; ch < Gm::NCH; ++ch) {
                     if (ch < nch) {
@@ -277,13 +258,10 @@ void gdws_fused_kernel(FusedParams params)
 #pragma unroll
                         for (int k = 0; k < kMaxEnt; ++k)
                             if (k < nent) *(u32x4_t *)(dst + k * PSTEP * Gm::PSW + ch * (Gm::CC / 2)) = v[ch & 1][k];
-                        GDWS_STAMP(12 + 2 * ch);
                         __syncthreads();  // chunk ch of stage st is in LDS
-                        GDWS_STAMP(13 + 2 * ch);
                         if (ch + 2 < Gm::NCH && ch + 2 < nch) issue(ch + 2);
                     }
                 }
-                GDWS_STAMP(3 + 2 * (st & 1));
             };
             run_stage(0, p.c_begin0, p.c_count0, std::true_type{});
             if constexpr (!SELF) {
@@ -371,7 +349,6 @@ void gdws_fused_kernel(FusedParams params)
 #pragma unroll
         for (int i = 0; i < 16; ++i) zero[i] = 0.f;
 
-        GDWS_STAMP(1);
         constexpr bool kShare = STRIDE == 1;
         // LDS reads of the depthwise B operand run this many reads ahead
         constexpr int kReads = NPB * (kShare ? 6 : 9);  // LDS reads per row block
@@ -393,11 +370,9 @@ void gdws_fused_kernel(FusedParams params)
                 ++stage;
                 buf = lds + (stage & 1) * p.stage_w;
             }
-            GDWS_STAMP(12 + 2 * idx);
             if constexpr (!SELF) {  // (without loader waves the whole stage is in LDS before the first row block)
                 for (int w = 0; w < nwait; ++w) __syncthreads();  // the chunks the window lies in have landed
             }
-            GDWS_STAMP(13 + 2 * idx);
             // A window starts at a multiple of four channels, so a lane's 16 bytes are 8-byte aligned (the compiler
             // then reads them as a pair of 8-byte halves; at a 16-byte aligned address that is as fast as one
             // 16-byte read, at the others the hardware takes a slower path).
@@ -548,12 +523,10 @@ void gdws_fused_kernel(FusedParams params)
                     }
             }
         }
-        GDWS_STAMP(2);
         if constexpr (!SELF) {
             for (int w = 0; w < p.final_waits; ++w) __syncthreads();  // chunks that no row block needed
         }
         __syncthreads();  // every wave is done with the input: the tile may overwrite it
-        GDWS_STAMP(3);
 
         // ---- epilogue, part 1 (compute waves): residual, ReLU, rounding; the tile goes to LDS ----
         if (NHWC && !GDWONLY && threadIdx.x < kTilePx) {
@@ -596,12 +569,10 @@ void gdws_fused_kernel(FusedParams params)
             else if (p.relu) to_lds(false_type{}, true_type{});
             else to_lds(false_type{}, false_type{});
         }
-        GDWS_STAMP(4);
     }
 
     // ---- epilogue, part 2 (all eight waves): LDS -> global in 16-byte pieces ----
     __syncthreads();
-    GDWS_STAMP(10);
     if (GDWONLY) return;
     const int t = threadIdx.x;
     // eight values of a tile row: as stored (no residual), or fp32 + residual, ReLU, rounding
@@ -697,7 +668,6 @@ void gdws_fused_kernel(FusedParams params)
             }
         }
     }
-    GDWS_STAMP(11);
 }
 
 // One launcher per (dtype, stride); each lives in a source file of its own so that the instances compile in parallel.
@@ -735,12 +705,8 @@ int launch_dispatch(const FusedParams &p, int TW, bool big, int mb, bool nhwc, i
         return launch_instance<DTYPE, tw, STRIDE, bg, 2, true, false, 1, true>(p, grid, lds_bytes, s);    \
     if (TW == tw && big == bg && mb == 0 && nhwc && npb == 1)                                         \
         return launch_instance<DTYPE, tw, STRIDE, bg, 2, true, true, 1, true>(p, grid, lds_bytes, s);
-#ifdef GDWS_ONLY_TW16
-            GDWS_CASE_SELF(16, false) GDWS_CASE_SELF(16, true)
-#else
             GDWS_CASE_SELF(4, false) GDWS_CASE_SELF(4, true) GDWS_CASE_SELF(8, false) GDWS_CASE_SELF(8, true)
             GDWS_CASE_SELF(16, false) GDWS_CASE_SELF(16, true) GDWS_CASE_SELF(32, false) GDWS_CASE_SELF(32, true)
-#endif
 #undef GDWS_CASE_SELF
             return GDWS_EUNSUPPORTED;
         }
@@ -766,11 +732,7 @@ int launch_dispatch(const FusedParams &p, int TW, bool big, int mb, bool nhwc, i
     GDWS_CASE(tw, true, 4, true, 2) GDWS_CASE_GDW(tw, false, 2) GDWS_CASE_GDW(tw, true, 2)                \
     GDWS_CASE(tw, false, 4, true, 1) GDWS_CASE(tw, true, 4, true, 1) GDWS_CASE(tw, false, 2, true, 1)     \
     GDWS_CASE(tw, true, 2, true, 1) GDWS_CASE_GDW(tw, false, 1) GDWS_CASE_GDW(tw, true, 1)
-#ifdef GDWS_ONLY_TW16  // (quick builds of one tile width while developing)
-    GDWS_CASES(16)
-#else
     GDWS_CASES_NARROW(4) GDWS_CASES(8) GDWS_CASES(16) GDWS_CASES(32)
-#endif
 #undef GDWS_CASES_NARROW
 #undef GDWS_CASES
 #undef GDWS_CASE_GDW

@@ -17,10 +17,6 @@ constexpr int kSmallGrid = 160;  // workgroups: below this a 256-CU chip is left
 constexpr int kFullGrid = 256;   // workgroups: one per CU
 constexpr int kWindowAlign = 4;  // channels: a window's 16-byte LDS reads are then 8-byte aligned
 
-#ifdef GDWS_TIMING
-unsigned long long *g_stamps = nullptr;
-#endif
-
 uint16_t to_half_bits(float v, int dtype)
 {
     if (dtype == GDWS_BF16) return float_to_bf16(v);
@@ -333,9 +329,6 @@ int launch_fused(const FusedArgs &a, hipStream_t s)
     const int tiles_n = (a.N + tc.TN - 1) / tc.TN;
     const dim3 grid((unsigned)((int64_t)p.tiles_x * p.tiles_y * tiles_n),
                     sc.gdw_only ? 1u : (unsigned)(sc.m_blocks_pad / mb));
-#ifdef GDWS_TIMING
-    p.stamps = g_stamps;
-#endif
     fused_launcher_t fn;
     if (a.dtype == GDWS_BF16) fn = a.stride == 1 ? launch_fused_bf16_s1 : launch_fused_bf16_s2;
     else fn = a.stride == 1 ? launch_fused_f16_s1 : launch_fused_f16_s2;
@@ -345,9 +338,5 @@ int launch_fused(const FusedArgs &a, hipStream_t s)
                       tc.lds_bytes <= (size_t)kMaxLds / 3;
     return fn(p, tc.TW, sc.big, sc.gdw_only ? 0 : mb, nhwc, npb, self, grid, tc.lds_bytes, s);
 }
-
-#ifdef GDWS_TIMING
-extern "C" void gdws_timing_buffer(unsigned long long *dev) { g_stamps = dev; }
-#endif
 
 }  // namespace gdws

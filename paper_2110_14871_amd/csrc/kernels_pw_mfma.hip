@@ -412,6 +412,7 @@ int launch_pw_mfma_f32(const PwArgs &a, hipStream_t s)
 int launch_pw_mfma(const PwMfmaArgs &a, hipStream_t s)
 {
     const PwMfmaTables &tb = *a.tables;
+    if (a.P >= ((int64_t)1 << 31)) return GDWS_EUNSUPPORTED;  // the kernel counts pixels in 32 bits
     PwParams p;
     p.t = (const uint16_t *)a.t; p.y = (uint16_t *)a.y; p.residual = (const uint16_t *)a.ep.residual;
     p.bias = tb.d_bias_pad; p.frag = (const u32x4_t *)tb.d_frag;

@@ -143,10 +143,12 @@ void mego(const double *sigma, const int32_t *rank, int C, int R, const double *
     }
 }
 
-// Algorithm 2 in the reading of Theorem 2's proof: starting from the ranks, drop the
-// filter with the smallest alpha_c * sigma_{g_c,c}^2 while the dropped total stays <= beta^2.
+// Algorithm 2: starting from the ranks, drop the filter with the smallest alpha_c * sigma_{g_c,c}^2 while the
+// dropped total stays within the bound.  The bound has two readings.  listing == false (Theorem 2 and its proof):
+// the total of dropped squared terms stays <= beta^2.  listing == true (the algorithm box taken literally): the
+// running total is compared with beta itself, strictly.
 void lego(const double *sigma, const int32_t *rank, int C, int R, const double *alpha, double beta, int g_min,
-          int32_t *g)
+          bool listing, int32_t *g)
 {
     for (int c = 0; c < C; ++c) g[c] = std::min(rank[c], R);
     double dropped = 0.0;
@@ -159,9 +161,46 @@ void lego(const double *sigma, const int32_t *rank, int C, int R, const double *
             const double v = (alpha ? alpha[c] : 1.0) * s * s;
             if (v < term) { term = v; best = c; }
         }
-        if (best < 0 || dropped + term > beta * beta) break;
+        if (best < 0) break;
+        if (listing ? !(dropped + term < beta) : dropped + term > beta * beta) break;
         dropped += term;
         --g[best];
+    }
+}
+
+// eq. 3 against eq. 2: the largest G with G (K^2 + M) <= rho C K^2 M, kept within [C, min(K^2, M) C] so that every
+// channel can hold at least one filter and none more than its slice's largest possible rank.
+int64_t budget_gamma(double rho, int C, int K, int M)
+{
+    const double kk = (double)K * K;
+    const int64_t gam = (int64_t)std::floor(rho * C * kk * M / (kk + M) + 1e-9);
+    const int64_t cap = (int64_t)std::min(K * K, M) * C;
+    return std::max<int64_t>(C, std::min(cap, gam));
+}
+
+// Appendix B: an intermediate channel whose depthwise filter is all zero produces a zero map, and one whose
+// pointwise column is all zero is never read; either way it adds nothing to the output and is dropped.
+void compact_factors(int C, int M, int KK, const int32_t *g, const float *dw, const float *pw, std::vector<int32_t> &g_out,
+                     std::vector<float> &dw_out, std::vector<float> &pw_out, std::vector<int32_t> &keep)
+{
+    int G = 0;
+    for (int c = 0; c < C; ++c) G += g[c];
+    g_out.assign(C, 0);
+    keep.clear();
+    int j = 0;
+    for (int c = 0; c < C; ++c)
+        for (int i = 0; i < g[c]; ++i, ++j) {
+            bool filter = false, column = false;
+            for (int k = 0; k < KK && !filter; ++k) filter = dw[(size_t)j * KK + k] != 0.f;
+            for (int m = 0; m < M && !column; ++m) column = pw[(size_t)m * G + j] != 0.f;
+            if (filter && column) { keep.push_back(j); ++g_out[c]; }
+        }
+    const int Gk = (int)keep.size();
+    dw_out.resize((size_t)Gk * KK);
+    pw_out.resize((size_t)M * Gk);
+    for (int q = 0; q < Gk; ++q) {
+        std::copy(dw + (size_t)keep[q] * KK, dw + (size_t)(keep[q] + 1) * KK, dw_out.begin() + (size_t)q * KK);
+        for (int m = 0; m < M; ++m) pw_out[(size_t)m * Gk + q] = pw[(size_t)m * G + keep[q]];
     }
 }
 

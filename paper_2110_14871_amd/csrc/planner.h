@@ -23,6 +23,10 @@ void factorise(const float *W, int M, int C, int K, const int32_t *g, const std:
 void mego(const double *sigma, const int32_t *rank, int C, int R, const double *alpha, int64_t gamma, int cap,
           int32_t *g);
 void lego(const double *sigma, const int32_t *rank, int C, int R, const double *alpha, double beta, int g_min,
-          int32_t *g);
+          bool listing, int32_t *g);
+int64_t budget_gamma(double rho, int C, int K, int M);
+// g_out [C], the kept filters / columns, keep [G']: index in the original of each kept intermediate channel
+void compact_factors(int C, int M, int KK, const int32_t *g, const float *dw, const float *pw, std::vector<int32_t> &g_out,
+                     std::vector<float> &dw_out, std::vector<float> &pw_out, std::vector<int32_t> &keep);
 
 }  // namespace gdws

@@ -9,7 +9,7 @@ def build_network(shapes, dtype, layout):
     for l in shapes:
         if l.kind == "gdws":
             W, b = workloads.configs.layer_tensors(l)
-            g = workloads.configs.draw_g(l)
+            g = workloads.configs.draw_g(l, gd.gdws_budget_gamma)
             desc = gd.make_desc(l.C, l.M, l.K, l.stride, l.pad, dtype, layout, l.relu, l.bias, l.residual is not None)
             plan = gd.gdws_plan(desc, g, W=W, bias=b)
             dw, pw = gd.gdws_plan_factors(plan)

@@ -198,9 +198,11 @@ def test_shape_sweep(case, dtype, layout, mode):
 def _config2_g(kind, c2):
     if kind == "budget":
         s, r = gd.gdws_singular_values(c2["Wt"])
-        g = gd.gdws_mego(s, r, c2["gamma"], g_init=np.ones(128, np.int32), cap=9)
+        gamma = gd.gdws_budget_gamma(c2["rho"], 128, 3, 128)
+        assert gamma == oracle.gamma_from_budget(c2["rho"], 128, 3, 128)
+        g = gd.gdws_mego(s, r, gamma, g_init=np.ones(128, np.int32), cap=9)
         _, S, _ = oracle.svd_slices(c2["Wt"])
-        assert (g == oracle.mego(S, c2["gamma"], g_init=np.ones(128, np.int32), cap=9, dim=128)).all()
+        assert (g == oracle.mego(S, gamma, g_init=np.ones(128, np.int32), cap=9, dim=128)).all()
         assert g.sum() == 269
         return g
     return np.full(128, 9 if kind == "all9" else 1, np.int32)

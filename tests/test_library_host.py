@@ -56,6 +56,32 @@ def test_greedy_allocations_match_oracle_bit_for_bit(seed):
     for beta in (0.0, 0.1 * emax, 0.5 * emax, 0.99 * emax, 1.01 * emax):
         assert (gd.gdws_lego(s, r, beta) == oracle.lego(S, beta, dim=M)).all()
         assert (gd.gdws_lego(s, r, beta, alpha, g_min=1) == oracle.lego(S, beta, alpha, g_min=1, dim=M)).all()
+        # the algorithm-box reading of the bound (no printed value pins either side: the two are only compared)
+        assert (gd.gdws_lego(s, r, beta, compare=gd.LEGO_LISTING) == oracle.lego(S, beta, compare="beta", dim=M)).all()
+
+
+def test_budget_gamma_matches_oracle():
+    for rho, C, K, M in [(0.25, 128, 3, 128), (0.4, 64, 3, 64), (0.4, 3, 3, 64), (0.4, 512, 3, 512), (1.0, 4, 3, 16),
+                         (5.0, 4, 3, 16), (0.0, 7, 5, 3), (0.4, 256, 3, 512), (0.1, 16, 1, 8)]:
+        assert gd.gdws_budget_gamma(rho, C, K, M) == oracle.gamma_from_budget(rho, C, K, M)
+    assert gd.gdws_budget_gamma(0.25, 128, 3, 128) == 269
+    assert gd.lib().gdws_budget_gamma(-1.0, 4, 3, 4) == -1 and gd.lib().gdws_budget_gamma(0.5, 0, 3, 4) == -1
+
+
+@pytest.mark.parametrize("seed,M,C,K,keep", [(420, 16, 12, 3, 0.05), (421, 64, 24, 3, 0.02), (422, 4, 3, 2, 0.1)])
+def test_sparse_aware_reduction_matches_oracle(seed, M, C, K, keep):
+    """gdws_compact_factors against the oracle's reduction, bit for bit, on the oracle's factors of a pruned W."""
+    import workloads
+    W = workloads.pruned_weight(seed, M, C, K, keep)
+    g_full = np.full(C, min(M, K * K), np.int32)
+    D, Pw = oracle.truncated_factors(W, g_full)
+    D, Pw = D.astype(np.float32), Pw.astype(np.float32)
+    g2, D2, Pw2, keep2 = oracle.compact_factors(g_full, D, Pw)
+    g3, D3, Pw3, keep3 = gd.gdws_compact_factors(g_full, D, Pw)
+    assert (g3 == g2).all() and (keep3 == keep2).all()
+    assert (D3 == D2.astype(np.float32)).all() and (Pw3 == Pw2.astype(np.float32)).all()
+    s, r = gd.gdws_singular_values(W)
+    assert (r == oracle.sparse_g(W)).all() and (g3 == r).all()
 
 
 def test_argument_errors_are_reported_not_thrown():
@@ -67,7 +93,8 @@ def test_argument_errors_are_reported_not_thrown():
     vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
     assert L.gdws_mego(vp(s), vp(r), 0, 4, None, 3, 0, vp(g)) == -1
     assert L.gdws_mego(vp(s), vp(r), 2, 4, None, -1, 0, vp(g)) == -1
-    assert L.gdws_lego(vp(s), vp(r), 2, 4, None, -0.5, 0, vp(g)) == -1
+    assert L.gdws_lego(vp(s), vp(r), 2, 4, None, -0.5, 0, 0, vp(g)) == -1
+    assert L.gdws_lego(vp(s), vp(r), 2, 4, None, 0.5, 0, 2, vp(g)) == -1       # unknown reading of the bound
     d = gd.make_desc(4, 4, 3, 1, 1)
     h = ctypes.c_void_p()
     assert L.gdws_plan(None, vp(g), None, None, None, None, ctypes.byref(h)) == -2

@@ -129,6 +129,62 @@ def test_worked_example_from_the_paper():
     assert macs == 9 * 32
 
 
+def test_worked_example_through_the_sparse_aware_reduction():
+    """Appendix B from the other side: start from the exact g_c = K^2 = 4 of Lemma 1 on the pruned toy weight and
+    let the reduction drop the dead channels: what is left is the printed g = [2,1,1] with the printed factors."""
+    t = _read_toy()
+    w1, w2, w3, w4 = t["w"]
+    Wm = np.zeros((4, 12))
+    Wm[0, 0], Wm[1, 4], Wm[2, 8], Wm[3, 2] = w1, w2, w3, w4
+    W = Wm.reshape(4, 3, 2, 2)
+    assert oracle.sparse_g(W).tolist() == [int(v) for v in t["g"]]
+    g_full = np.full(3, 4, np.int32)
+    D, Pw = oracle.truncated_factors(W, g_full)
+    assert oracle.macs_gdws(g_full, 2, 4, 1, 1) == 4 * 12 + 12 * 4            # exact but dearer than the dense 48
+    g2, D2, Pw2, keep = oracle.compact_factors(g_full, D, Pw)
+    assert g2.tolist() == [int(v) for v in t["g"]] and keep.tolist() == [0, 1, 4, 8]
+    assert np.abs(Pw2 - np.array(t["pw"])).max() < 1e-14
+    assert np.abs(D2.reshape(4, 4) - np.array(t["gdw"]).reshape(4, 3, 4)[np.arange(4), [0, 0, 1, 2]]).max() < 1e-14
+    assert oracle.weight_error(W, oracle.expand_weight(D2, Pw2, g2)) < 1e-14
+    assert oracle.macs_gdws(g2, 2, 4, 1, 1) == t["macs_gdws"][0]
+    assert np.count_nonzero(Pw2) + np.count_nonzero(D2) == t["nonzeros"][0]
+
+
+@pytest.mark.parametrize("seed,M,C,K,keep", [(370, 16, 12, 3, 0.05), (371, 64, 24, 3, 0.02), (372, 8, 6, 2, 0.15)])
+def test_sparse_aware_reduction_on_pruned_weights(seed, M, C, K, keep):
+    """Pruned W: g_c = rank(W_c) is exact (Lemma 1); dropping dead channels changes neither the product W_P W_D nor
+    the output, only the MAC count; rank(W_c) is bounded by the slice's non-zero rows and columns."""
+    W = workloads.pruned_weight(seed, M, C, K, keep).astype(np.float64)
+    Wc = oracle.slices(W)
+    r = oracle.sparse_g(W)
+    for c in range(C):
+        assert r[c] == np.linalg.matrix_rank(Wc[c])
+        assert r[c] <= min(np.count_nonzero(np.abs(Wc[c]).sum(0)), np.count_nonzero(np.abs(Wc[c]).sum(1)))
+    assert r.sum() < C * min(M, K * K)                       # the pruning did lower some ranks
+    _, S, _ = oracle.svd_slices(W)
+    assert (oracle.lego(S, 0.0, dim=max(M, K * K)) == r).all()
+    g_full = np.full(C, min(M, K * K), np.int32)
+    D, Pw = oracle.truncated_factors(W, g_full)
+    g2, D2, Pw2, keep_idx = oracle.compact_factors(g_full, D, Pw)
+    assert (g2 == r).all() and len(keep_idx) == r.sum()
+    h = oracle.offsets(g_full)
+    for q, j in enumerate(keep_idx):                         # kept channels are the leading ones of each slice
+        c = oracle.chan_of(g_full)[j]
+        assert j - h[c] < r[c]
+    assert oracle.weight_error(W, oracle.expand_weight(D2, Pw2, g2)) < 1e-12
+    x = rng.normal(seed + 5, (2, C, 6, 5)).astype(np.float64)
+    y_full, m_full = oracle.gdws_forward(x, g_full, D, Pw, stride=1, pad=1, return_macs=True)
+    y_red, m_red = oracle.gdws_forward(x, g2, D2, Pw2, stride=1, pad=1, return_macs=True)
+    assert np.abs(y_full - y_red).max() < 1e-13 and m_red < m_full
+    assert m_red == oracle.macs_gdws(g2, K, M, 6 + 2 - K + 1, 5 + 2 - K + 1) * 2
+    assert np.abs(y_red - oracle.conv_dense(x, W, stride=1, pad=1)).max() < 1e-12
+    # a zero pointwise column is dead as well, and zeros elsewhere are not
+    Pw3 = Pw2.copy()
+    Pw3[:, 0] = 0.0
+    g3, _, _, k3 = oracle.compact_factors(g2, D2, Pw3)
+    assert g3.sum() == g2.sum() - 1 and 0 not in k3
+
+
 def _all_g(ranks):
     return itertools.product(*[range(r + 1) for r in ranks])
 
@@ -180,7 +236,9 @@ def test_mego_with_floor_and_cap_and_budget():
     taken = sorted((S[c, i] ** 2 for c in range(8) for i in range(1, g[c])), reverse=True)
     left = max(S[c, g[c]] ** 2 for c in range(8) if g[c] < 9)
     assert not taken or taken[-1] >= left
+    # eq. 3 against eq. 2 by brute force: the largest G whose MACs fit, then the clamp to [C, min(K^2, M) C]
     for rho, C, K, M in [(0.25, 128, 3, 128), (0.4, 64, 3, 64), (0.4, 3, 3, 64), (0.4, 512, 3, 512), (1.0, 4, 3, 16)]:
-        assert oracle.gamma_from_budget(rho, C, K, M) == workloads.budget_gamma(rho, C, K, M)
+        fits = max(G for G in range(0, 9 * C + 2) if G * (K * K + M) <= rho * C * K * K * M)
+        assert oracle.gamma_from_budget(rho, C, K, M) == max(C, min(min(K * K, M) * C, fits))
     assert oracle.gamma_from_budget(0.25, 128, 3, 128) == 269
     assert oracle.gamma_from_budget(1.0, 4, 3, 16) == 23 and oracle.gamma_from_budget(5.0, 4, 3, 16) == 36

@@ -50,7 +50,6 @@ def test_config_shapes():
     c1 = workloads.config1()
     assert c1["X"].shape == (1, 16, 32, 32) and c1["Wt"].shape == (32, 16, 3, 3)
     assert set(np.unique(c1["g"])) <= {1, 2, 3}
-    assert workloads.budget_gamma(0.25, 128, 3, 128) == 269
     v = workloads.vgg16_shape()
     assert sum(l.kind == "gdws" for l in v) == 13 and sum(l.kind == "maxpool" for l in v) == 5
     assert (v[-1].Ho, v[-1].Wo) == (1, 1)

@@ -8,5 +8,5 @@ from .rng import normal, uniform_int, geometric, bits64          # noqa: F401
 from .storage import to_storage, from_storage, storage_bytes     # noqa: F401
 from .configs import (                                           # noqa: F401
     LayerShape, config1, config2, vgg16_shape, resnet18_shape, resnet50_shape,
-    he_weight, budget_gamma, skewed_g,
+    he_weight, skewed_g, draw_g, pruned_weight,
 )

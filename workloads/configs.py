@@ -56,15 +56,15 @@ def small_bias(seed, M):
     return rng.normal(seed, (M,), std=0.05)
 
 
-def budget_gamma(rho, C, K, M):
-    """Largest total multiplier whose depthwise+pointwise MACs fit a fraction rho of the dense MACs.
+def pruned_weight(seed, M, C, K, keep=0.02):
+    """[M, C, K, K] fp32: a He-initialised weight with all but a fraction `keep` of its entries set to zero.
 
-    G (K^2 + M) <= rho C K^2 M, clamped so that every channel can keep at least
-    one filter and none needs more than K^2 (or M if that is smaller).
+    Stands in for an unstructured-pruned layer (the paper prunes to 90 - 99 % sparsity): the surviving
+    entries are scattered, so no filter is all zero, yet every M x K^2 slice has few non-zero columns.
     """
-    gam = int(np.floor(rho * C * K * K * M / (K * K + M) + 1e-9))
-    cap = min(K * K, M)
-    return max(C, min(cap * C, gam))
+    W = he_weight(seed, M, C, K)
+    u = rng.bits64(seed + 1, 0, W.size).astype(np.float64) / 2.0 ** 64
+    return (W * (u.reshape(W.shape) < keep)).astype(np.float32)
 
 
 def skewed_g(seed, C, gamma, cap=9, p=0.5):
@@ -90,8 +90,13 @@ def skewed_g(seed, C, gamma, cap=9, p=0.5):
     return g.astype(np.int32)
 
 
-def draw_g(layer: LayerShape):
-    """Per-channel multipliers for a "gdws" layer according to its g_rule."""
+def draw_g(layer: LayerShape, budget_gamma=None):
+    """Per-channel multipliers for a "gdws" layer according to its g_rule.
+
+    The "skewed:rho" rule needs the total multiplier that a fraction rho of the dense layer's
+    MACs allows; that figure is the method's arithmetic, so the caller supplies it as
+    budget_gamma(rho, C, K, M) (the library's planner on the GPU side, the oracle on the CPU side).
+    """
     cap = min(layer.K * layer.K, layer.M)
     rule = layer.g_rule
     if rule.startswith("uniform"):           # "uniform:lo:hi"
@@ -99,7 +104,9 @@ def draw_g(layer: LayerShape):
         return np.minimum(rng.uniform_int(layer.seed + 2, (layer.C,), int(lo), int(hi)), cap).astype(np.int32)
     if rule.startswith("skewed"):            # "skewed:rho"
         rho = float(rule.split(":")[1])
-        return skewed_g(layer.seed + 2, layer.C, budget_gamma(rho, layer.C, layer.K, layer.M), cap=cap)
+        if budget_gamma is None:
+            raise ValueError("the skewed rule needs the caller's budget_gamma(rho, C, K, M)")
+        return skewed_g(layer.seed + 2, layer.C, int(budget_gamma(rho, layer.C, layer.K, layer.M)), cap=cap)
     raise ValueError(rule)
 
 
@@ -126,13 +133,13 @@ def config2(N=256):
     """bf16 layer: X [N,128,16,16] ~ N(0,1), W [128,128,3,3] ~ N(0, 0.05^2); g is chosen by the caller.
 
     The caller derives g from the singular values of W for a 25 % MAC budget
-    (total multiplier budget_gamma(0.25, 128, 3, 128) = 269), or uses the
+    (`rho`; the total multiplier that budget allows is 269), or uses the
     all-9 / all-1 edge cases.
     """
     X = rng.normal(11, (N, 128, 16, 16))
     W = rng.normal(12, (128, 128, 3, 3), std=0.05)
     return dict(N=N, C=128, H=16, W=16, M=128, K=3, stride=1, pad=1, dtype="bf16", X=X, Wt=W,
-                gamma=budget_gamma(0.25, 128, 3, 128))
+                rho=0.25)
 
 
 # --------------------------------------------------------------------------
