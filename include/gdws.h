@@ -63,6 +63,7 @@ typedef struct {
 
 typedef struct gdws_plan_s gdws_plan_t;
 typedef struct gdws_net_s gdws_net_t;
+typedef struct gdws_graph_s gdws_graph_t;
 
 const char *gdws_strerror(int code);
 
@@ -223,6 +224,28 @@ size_t gdws_net_workspace_bytes(const gdws_net_t *net, int32_t N, int32_t H, int
 /* Runs every node in order on `stream`; y receives the last node's output. */
 int gdws_network_forward(const gdws_net_t *net, const void *x, void *y, int32_t N, int32_t H, int32_t W,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- launch graphs (Appendix A, the frames-per-second protocol) ------------------ */
+
+/* The paper measures whole-network inference at batch 1 (5000 warm-up and 10000
+ * timed forwards between device events).  At that size a forward is a chain of
+ * some twenty short kernels and the host's launch calls dominate, so the chain
+ * is recorded once and replayed as one launch.
+ *
+ * gdws_capture_begin puts `stream` (not the default stream) into capture mode:
+ * forward calls of this library issued on it from the calling thread are then
+ * recorded instead of run.  gdws_capture_end ends the capture and returns the
+ * instantiated graph.  Every forward call to be recorded must have run once,
+ * eagerly, with the same arguments before (the first launch of a kernel sets a
+ * function attribute, which is not a stream operation).  The graph holds the
+ * device pointers passed to the recorded calls: the buffers must stay allocated,
+ * and a replay reads and writes them where they are.  No memset node is ever
+ * recorded: no forward call of this library clears memory through the runtime. */
+int gdws_capture_begin(void *stream);
+int gdws_capture_end(void *stream, gdws_graph_t **out);
+/* Replays the recorded launches on `stream`, in their recorded order. */
+int gdws_graph_launch(const gdws_graph_t *graph, void *stream);
+int gdws_graph_destroy(gdws_graph_t *graph);
 
 #ifdef __cplusplus
 }

@@ -72,6 +72,10 @@ def lib():
             "gdws_net_destroy": (ctypes.c_int, [vp]),
             "gdws_net_workspace_bytes": (sz, [vp, i32, i32, i32]),
             "gdws_network_forward": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp, sz, vp]),
+            "gdws_capture_begin": (ctypes.c_int, [vp]),
+            "gdws_capture_end": (ctypes.c_int, [vp, ctypes.POINTER(vp)]),
+            "gdws_graph_launch": (ctypes.c_int, [vp, vp]),
+            "gdws_graph_destroy": (ctypes.c_int, [vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -85,7 +89,8 @@ EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_mego", "gdws_lego", "g
            "gdws_plan_info", "gdws_plan_factors", "gdws_intermediate_channels", "gdws_workspace_bytes", "gdws_forward",
            "gdws_forward_maxpool2", "gdws_gdw_forward",
            "gdws_pw_forward", "conv_dense_workspace_bytes", "conv_dense_forward", "gdws_net_create",
-           "gdws_net_destroy", "gdws_net_workspace_bytes", "gdws_network_forward")
+           "gdws_net_destroy", "gdws_net_workspace_bytes", "gdws_network_forward", "gdws_capture_begin",
+           "gdws_capture_end", "gdws_graph_launch", "gdws_graph_destroy")
 
 
 def _check(code, where):
@@ -345,3 +350,41 @@ def gdws_network_forward(net, x, y, N, H, W, workspace=None, stream=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().gdws_network_forward(net.handle, _dev(x), _dev(y), N, H, W, _dev(workspace), ws_bytes,
                                       _stream(stream)), "gdws_network_forward")
+
+
+# ---- launch graphs ------------------------------------------------------------------
+
+class Graph:
+    """Owner of a gdws_graph_t handle."""
+
+    def __init__(self, handle):
+        self.handle = handle
+
+    def destroy(self):
+        if self.handle:
+            lib().gdws_graph_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def gdws_capture_begin(stream):
+    _check(lib().gdws_capture_begin(_stream(stream)), "gdws_capture_begin")
+
+
+def gdws_capture_end(stream):
+    h = ctypes.c_void_p()
+    _check(lib().gdws_capture_end(_stream(stream), ctypes.byref(h)), "gdws_capture_end")
+    return Graph(h)
+
+
+def gdws_graph_launch(graph, stream=None):
+    _check(lib().gdws_graph_launch(graph.handle, _stream(stream)), "gdws_graph_launch")
+
+
+def gdws_graph_destroy(graph):
+    graph.destroy()

@@ -832,3 +832,57 @@ int gdws_network_forward(const gdws_net_t *net, const void *x, void *y, int32_t 
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------------
+// launch graphs (the batch-1 protocol of Appendix A: a whole forward replayed as one graph launch)
+// ---------------------------------------------------------------------------------
+
+struct gdws_graph_s {
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    ~gdws_graph_s()
+    {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+    }
+};
+
+extern "C" {
+
+int gdws_capture_begin(void *stream)
+{
+    if (!stream) return GDWS_EINVAL;  // the default stream cannot be captured
+    GDWS_HIP_CHECK(hipStreamBeginCapture((hipStream_t)stream, hipStreamCaptureModeThreadLocal));
+    return GDWS_OK;
+}
+
+int gdws_capture_end(void *stream, gdws_graph_t **out)
+{
+    GDWS_TRY
+    if (!stream) return GDWS_EINVAL;
+    hipGraph_t graph = nullptr;
+    const hipError_t e = hipStreamEndCapture((hipStream_t)stream, &graph);  // (always ends the capture)
+    if (!out) { if (graph) (void)hipGraphDestroy(graph); return GDWS_ENULL; }
+    if (e != hipSuccess || !graph) return GDWS_EHIP;
+    std::unique_ptr<gdws_graph_t> g(new gdws_graph_t);
+    g->graph = graph;
+    GDWS_HIP_CHECK(hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0));
+    *out = g.release();
+    return GDWS_OK;
+    GDWS_CATCH
+}
+
+int gdws_graph_launch(const gdws_graph_t *graph, void *stream)
+{
+    if (!graph) return GDWS_ENULL;
+    GDWS_HIP_CHECK(hipGraphLaunch(graph->exec, (hipStream_t)stream));
+    return GDWS_OK;
+}
+
+int gdws_graph_destroy(gdws_graph_t *graph)
+{
+    delete graph;
+    return GDWS_OK;
+}
+
+}  // extern "C"
