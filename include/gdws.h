@@ -173,6 +173,21 @@ int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32
  * for the matrix-core pointwise kernel).  0 if plan is NULL. */
 int32_t gdws_intermediate_channels(const gdws_plan_t *plan);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): gdws_forward in
+ * GDWS_MODE_UNFUSED with the G-channel intermediate held in a device array that
+ * is part of the library image (GDWS_STATIC_SCRATCH_BYTES per GPU, resident from
+ * the library's load to the end of the process) instead of a caller's workspace.
+ * Calls no allocating routine.  GDWS_EWORKSPACE if the intermediate, N x Gt x H'
+ * x W' elements of the plan's dtype (Gt = gdws_intermediate_channels), does not
+ * fit.  All calls on one GPU share that one array: calls that may overlap in time
+ * on a GPU (different streams, different host threads) race and must be ordered
+ * by the caller.  Results are those of gdws_forward(..., GDWS_MODE_UNFUSED), bit
+ * for bit. */
+#define GDWS_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int gdws_forward_static(const gdws_plan_t *plan, const void *x, const void *residual, void *y, int32_t N,
+                        int32_t H, int32_t W, void *stream);
+
 /* The two stages on their own (Section 3.1 Definition: GDW, then PW).  Same
  * layouts; t dev [N,Gt,H',W'] / [N,H',W',Gt] in the plan's dtype with
  * Gt = gdws_intermediate_channels(plan).  gdws_pw_forward applies the plan's

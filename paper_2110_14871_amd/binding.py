@@ -64,6 +64,7 @@ def lib():
             "gdws_workspace_bytes": (sz, [vp, i32, i32, i32, ctypes.c_int]),
             "gdws_forward": (ctypes.c_int, [vp, vp, vp, vp, i32, i32, i32, vp, sz, ctypes.c_int, vp]),
             "gdws_forward_maxpool2": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp]),
+            "gdws_forward_static": (ctypes.c_int, [vp, vp, vp, vp, i32, i32, i32, vp]),
             "gdws_gdw_forward": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp]),
             "gdws_pw_forward": (ctypes.c_int, [vp, vp, vp, vp, i32, i32, i32, vp]),
             "conv_dense_workspace_bytes": (sz, [pdesc]),
@@ -87,7 +88,7 @@ def lib():
 EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_mego", "gdws_lego", "gdws_budget_gamma",
            "gdws_compact_factors", "gdws_plan_sparse", "gdws_plan", "gdws_plan_destroy",
            "gdws_plan_info", "gdws_plan_factors", "gdws_intermediate_channels", "gdws_workspace_bytes", "gdws_forward",
-           "gdws_forward_maxpool2", "gdws_gdw_forward",
+           "gdws_forward_maxpool2", "gdws_forward_static", "gdws_gdw_forward",
            "gdws_pw_forward", "conv_dense_workspace_bytes", "conv_dense_forward", "gdws_net_create",
            "gdws_net_destroy", "gdws_net_workspace_bytes", "gdws_network_forward", "gdws_capture_begin",
            "gdws_capture_end", "gdws_graph_launch", "gdws_graph_destroy")
@@ -275,6 +276,14 @@ def gdws_forward(plan, x, y, N, H, W, residual=None, workspace=None, mode=MODE_A
 def gdws_forward_maxpool2(plan, x, y, N, H, W, stream=None):
     _check(lib().gdws_forward_maxpool2(plan.handle, _dev(x), _dev(y), N, H, W, _stream(stream)),
            "gdws_forward_maxpool2")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def gdws_forward_static(plan, x, y, N, H, W, residual=None, stream=None):
+    _check(lib().gdws_forward_static(plan.handle, _dev(x), _dev(residual), _dev(y), N, H, W, _stream(stream)),
+           "gdws_forward_static")
 
 
 def gdws_gdw_forward(plan, x, t, N, H, W, stream=None):

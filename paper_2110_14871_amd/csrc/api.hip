@@ -886,3 +886,55 @@ int gdws_graph_destroy(gdws_graph_t *graph)
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------------
+// the forward pass for callers that cannot allocate: the intermediate lives in a static device array
+// ---------------------------------------------------------------------------------
+
+namespace {
+
+constexpr size_t kStaticScratchBytes = GDWS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU (every GPU holds its own copy)
+std::mutex g_scratch_mu;
+
+// The array's address on the current device, looked up once per device.  (In host code `scratch` itself is only
+// a handle for this lookup, never a device address.)
+int static_scratch(void **out)
+{
+    int dev = -1;
+    GDWS_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return GDWS_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        GDWS_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return GDWS_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return GDWS_OK;
+}
+
+}  // namespace
+
+extern "C" int gdws_forward_static(const gdws_plan_t *plan, const void *x, const void *residual, void *y, int32_t N,
+                                   int32_t H, int32_t W, void *stream)
+{
+    if (!plan || !x || !y) return GDWS_ENULL;
+    if (plan->desc.has_residual && !residual) return GDWS_ENULL;
+    int Ho, Wo;
+    int rc = check_image(plan->desc, N, H, W, &Ho, &Wo);
+    if (rc) return rc;
+    if (intermediate_bytes(plan, N, Ho, Wo) > kStaticScratchBytes) return GDWS_EWORKSPACE;
+    void *t = nullptr;
+    rc = static_scratch(&t);
+    if (rc) return rc;
+    // every element of the intermediate (its zero padding channels included) is written by the depthwise stage
+    // before the pointwise stage reads it: nothing of an earlier call's contents has to be cleared
+    rc = run_gdw(plan, x, t, N, H, W, Ho, Wo, (hipStream_t)stream);
+    if (rc) return rc;
+    return run_pw(plan, t, residual, y, N, Ho, Wo, (hipStream_t)stream);
+}
