@@ -6,6 +6,11 @@ over one batch of synthetic input already resident in HBM.  Default workload: th
 layer with C = M = 128 on 16 x 16 feature maps at batch 256, g from the greedy 25 % MAC
 budget (G = 269).  Prints ONE JSON line with images/s, the dominant kernel's roofline
 figures and the CPU oracle timed on the host cores.
+
+Clocks: `value` and `ms_per_step` are host wall time around the timed steps (synchronised on
+both sides); `roofline.kernel_ms` is device time between two events recorded on the launch
+stream around the same steps.  The steps are issued through a launch graph recorded once
+(one graph launch replays `--rotate` steps), unless --no-graph is given.
 """
 import argparse
 import json
@@ -18,21 +23,28 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0          # dense bf16 / fp16
+
+NETWORKS = {"vgg16": ("f16", 256, 32), "resnet18": ("bf16", 512, 32), "resnet50": ("bf16", 128, 224),
+            "wrn28_4": ("bf16", 256, 32)}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the workload's default)")
+    ap.add_argument("--warmup", type=int, default=-1, help="untimed steps before them (-1 = the workload's default)")
     ap.add_argument("--workload", default="config2",
-                    choices=["config2", "config2_g9", "config2_g1", "vgg16", "resnet18", "resnet50"],
-                    help="config2 (default, the headline layer) and its two sub-runs, or one of the network-shaped "
-                         "workloads (VGG-16 fp16 batch 256, ResNet-18 bf16 batch 512 at 32x32; ResNet-50 bf16 batch 128 "
-                         "at 224x224)")
-    ap.add_argument("--batch", type=int, default=0, help="network workloads: batch size (0 = the workload's own)")
+                    choices=["config2", "config2_g9", "config2_g1", "config2_dense"] + sorted(NETWORKS),
+                    help="config2 (default, the headline layer), its two sub-runs, the standard convolution it "
+                         "approximates (config2_dense: conv_dense_forward on the same shape), or a network-shaped "
+                         "workload (VGG-16 fp16 batch 256, ResNet-18 bf16 batch 512, WRN-28-4 bf16 batch 256 at 32x32; "
+                         "ResNet-50 bf16 batch 128 at 224x224)")
+    ap.add_argument("--batch", type=int, default=0, help="network workloads: batch size (0 = the workload's own); "
+                    "--batch 1 is the paper's frames-per-second protocol (5000 warm-up and 10000 timed forwards)")
     ap.add_argument("--layout", default="nhwc", choices=["nhwc", "nchw"])
     ap.add_argument("--mode", default="auto", choices=["auto", "fused", "unfused"])
+    ap.add_argument("--no-graph", action="store_true", help="issue every step with its own launch calls")
     ap.add_argument("--rotate", type=int, default=16,
                     help="number of distinct input/output buffer pairs cycled through (keeps the working set "
                          "larger than the 256 MB last-level cache so HBM is what is measured)")
@@ -47,63 +59,126 @@ def parse():
     return ap.parse_args()
 
 
-def clock_ramp(step, ramp_ms):
-    """Keep the GPU busy with step(i) for about ramp_ms so that its clocks are at their steady state."""
-    import torch
-    i, t0 = 0, time.perf_counter()
+class Stepper:
+    """Issues steps 0, 1, 2, ... on `stream`: step i is fn(i % period).  With a graph, `period` consecutive steps are
+    recorded once and replayed by one graph launch; what does not fill a whole period is issued eagerly."""
+
+    def __init__(self, gd, fn, period, stream, use_graph):
+        import torch
+        self.gd, self.fn, self.period, self.stream = gd, fn, period, stream
+        self.graph = None
+        self.next = 0
+        with torch.cuda.stream(stream):
+            for k in range(period):          # every recorded call must have run once, eagerly
+                fn(k)
+            stream.synchronize()
+            if use_graph:
+                gd.gdws_capture_begin(stream)
+                for k in range(period):
+                    fn(k)
+                self.graph = gd.gdws_capture_end(stream)
+
+    def run(self, n):
+        while n > 0:
+            if self.graph is not None and self.next % self.period == 0 and n >= self.period:
+                self.gd.gdws_graph_launch(self.graph, self.stream)
+                n -= self.period
+                self.next += self.period
+            else:
+                self.fn(self.next % self.period)
+                n -= 1
+                self.next += 1
+
+
+def clock_ramp(stepper, ramp_ms):
+    """Keep the GPU busy with steps for about ramp_ms so that its clocks are at their steady state."""
+    t0 = time.perf_counter()
     while (time.perf_counter() - t0) * 1e3 < ramp_ms:
-        for _ in range(50):
-            step(i)
-            i += 1
-        torch.cuda.synchronize()
+        stepper.run(4 * stepper.period)
+        stepper.stream.synchronize()
+    stepper.run((-stepper.next) % stepper.period)      # back to a period boundary
 
 
-def measured_traffic(workload, layout):
-    """HBM bytes per launch from the committed counter summary of this workload, or None."""
-    path = os.path.join(ROOT, "profiles", f"fused_{workload}_{layout}_hbm_traffic.txt")
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
-    except OSError:
-        pass
-    return None
-
-
-def run_network(a):
-    """Whole-network forward of a VGG-16 / ResNet-18 / ResNet-50 shaped stack (every 3x3 convolution a GDWS layer)."""
-    import numpy as np
+def timed(stepper, steps, warmup):
+    """(wall ms per step, device ms per step) of `steps` steps after `warmup` untimed ones."""
     import torch
-    import paper_2110_14871_amd as gd
-    import workloads
-    from gpu_util import empty_act, to_device
-    from net_util import build_network
-
-    torch.cuda.set_device(0)
-    dtype, batch, size, maker = {"vgg16": ("f16", 256, 32, workloads.vgg16_shape),
-                                 "resnet18": ("bf16", 512, 32, workloads.resnet18_shape),
-                                 "resnet50": ("bf16", 128, 224, workloads.resnet50_shape)}[a.workload]
-    N = a.batch or batch
-    shapes = maker(size, size)
-    net, _ = build_network(shapes, dtype, a.layout)
-    x, _ = to_device(workloads.rng.normal(900, (N, 3, size, size)), dtype, a.layout)
-    last = shapes[-1]
-    y = empty_act(N, last.M, last.Ho, last.Wo, dtype, a.layout)
-    ws = torch.empty(max(1, gd.gdws_net_workspace_bytes(net, N, size, size)), dtype=torch.uint8, device="cuda")
-    stream = torch.cuda.current_stream()
-    clock_ramp(lambda i: gd.gdws_network_forward(net, x, y, N, size, size, workspace=ws, stream=stream), a.ramp_ms)
-    for _ in range(a.warmup):
-        gd.gdws_network_forward(net, x, y, N, size, size, workspace=ws, stream=stream)
+    stream = stepper.stream
+    stepper.run(warmup)
+    stepper.run((-stepper.next) % stepper.period)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
-    for _ in range(a.steps):
-        gd.gdws_network_forward(net, x, y, N, size, size, workspace=ws, stream=stream)
+    stepper.run(steps)
     ev1.record(stream)
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / a.steps
-    dev_ms = ev0.elapsed_time(ev1) / a.steps
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    return wall_ms, ev0.elapsed_time(ev1) / steps
+
+
+def copy_rate_gbs(stream):
+    """Read + write rate of a plain 256 MiB device-to-device copy on this chip: the practical HBM ceiling."""
+    import torch
+    with torch.cuda.stream(stream):
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(10):
+            dst.copy_(src)
+        ev1.record(stream)
+        stream.synchronize()
+    return 2 * src.numel() * 10 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+
+
+def profile_traffic(workload, layout):
+    """HBM bytes per launch from the committed counter summary of this workload (rocprofv3 --pmc FETCH_SIZE and
+    WRITE_SIZE, separate runs), with the file it comes from; (None, None) if there is none."""
+    name = f"fused_{workload}_{layout}_hbm_traffic.txt"
+    try:
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1]), "profiles/" + name
+    except OSError:
+        pass
+    return None, None
+
+
+def oracle_threads():
+    import oracle
+    return min(oracle.max_threads(), os.cpu_count() or 1, 16)
+
+
+def run_network(a):
+    """Whole-network forward of a VGG-16 / ResNet-18 / ResNet-50 / WRN-28-4 shaped stack (every 3x3 convolution a GDWS layer)."""
+    import numpy as np
+    import torch
+    import paper_2110_14871_amd as gd
+    import workloads
+    from gpu_util import empty_act, from_device, rel_l2, to_device
+    from net_util import build_network
+
+    torch.cuda.set_device(0)
+    dtype, batch, size = NETWORKS[a.workload]
+    maker = {"vgg16": workloads.vgg16_shape, "resnet18": workloads.resnet18_shape, "resnet50": workloads.resnet50_shape,
+             "wrn28_4": workloads.wrn28_4_shape}[a.workload]
+    N = a.batch or batch
+    protocol = "batch-1 frames per second (5000 warm-up, 10000 timed forwards)" if N == 1 else "batched throughput"
+    steps = a.steps or (10000 if N == 1 else 20)
+    warmup = a.warmup if a.warmup >= 0 else (5000 if N == 1 else 3)
+    shapes = maker(size, size)
+    net, params = build_network(shapes, dtype, a.layout)
+    x, x_exact = to_device(workloads.rng.normal(900, (N, 3, size, size)), dtype, a.layout)
+    last = shapes[-1]
+    y = empty_act(N, last.M, last.Ho, last.Wo, dtype, a.layout)
+    ws = torch.empty(max(1, gd.gdws_net_workspace_bytes(net, N, size, size)), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.Stream()
+    stepper = Stepper(gd, lambda k: gd.gdws_network_forward(net, x, y, N, size, size, workspace=ws, stream=stream), 1,
+                      stream, not a.no_graph)
+    clock_ramp(stepper, a.ramp_ms)
+    wall_ms, dev_ms = timed(stepper, steps, warmup)
     # algorithmic traffic and work: every layer reads its input and writes its output once, plus the weights
     alg_bytes, flops = 0, 0.0
     for l in shapes:
@@ -117,15 +192,29 @@ def run_network(a):
             flops += 2.0 * px_out * l.M * l.C * l.K * l.K
             alg_bytes += 2 * l.M * l.C * l.K * l.K
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
-    print(json.dumps({
+    out = {
         "metric": "GDWS network images/sec", "value": N / (wall_ms * 1e-3), "unit": "images/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": wall_ms, "higher_is_better": True,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall_ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"{a.workload}-shaped network, batch {N}, {size}x{size} input, {len(shapes)} layers",
-                   "layout": a.layout, "clock_ramp_ms": a.ramp_ms},
+                   "layout": a.layout, "protocol": protocol, "launch": "eager" if a.no_graph else "launch graph",
+                   "clock_ramp_ms": a.ramp_ms, "value_clock": "host wall time", "kernel_ms_clock": "device events"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel_ms": dev_ms,
-                     "tflops": flops / (dev_ms * 1e-3) / 1e12, "algorithmic_bytes": alg_bytes}}))
+                     "tflops": flops / (dev_ms * 1e-3) / 1e12, "algorithmic_bytes": alg_bytes,
+                     "measured_copy_rate_gbs": copy_rate_gbs(stream)}}
+    if not a.no_cpu_baseline:
+        import oracle
+        pick = sorted({0, N - 1})
+        threads = oracle_threads()
+        t0 = time.perf_counter()
+        ref = oracle.network_forward(shapes, params, x_exact[pick], store=dtype, round_intermediate=dtype, threads=threads)
+        dt = time.perf_counter() - t0
+        yh = from_device(y, dtype, a.layout)[pick]
+        out["cpu_baseline"] = {"value": len(pick) / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
+                               "sample": f"images {pick} of the batch, one pass, fp64 direct loops with OpenMP, {dt:.2f} s",
+                               "rel_l2_gpu_vs_oracle": rel_l2(yh, ref)}
+    print(json.dumps(out))
 
 
 def main():
@@ -134,95 +223,111 @@ def main():
         print("bench.py: this build runs on one GPU only (the path needs no collective; batch shards would "
               "each run this same kernel) -- use --gpus 1", file=sys.stderr)
         sys.exit(2)
-
-    if a.workload in ("vgg16", "resnet18", "resnet50"):
-        if a.steps == 2000:
-            a.steps, a.warmup = 20, 3
+    if a.workload in NETWORKS:
         return run_network(a)
 
     import numpy as np
     import torch
     import paper_2110_14871_amd as gd
     import workloads
-    from gpu_util import empty_act, from_device, rel_l2, to_device
+    from gpu_util import empty_act, from_device, quantise, rel_l2, to_device
 
     torch.cuda.set_device(0)
+    steps = a.steps or 2000
+    warmup = a.warmup if a.warmup >= 0 else 200
     c2 = workloads.config2(N=256)
     N, C, H, W, M, K = c2["N"], c2["C"], c2["H"], c2["W"], c2["M"], c2["K"]
     dtype, b = "bf16", 2
-    if a.workload == "config2":
-        s, r = gd.gdws_singular_values(c2["Wt"])
-        g = gd.gdws_mego(s, r, gd.gdws_budget_gamma(c2["rho"], C, K, M), g_init=np.ones(C, np.int32), cap=9)
-    else:
-        g = np.full(C, 9 if a.workload == "config2_g9" else 1, np.int32)
-    G = int(g.sum())
-    desc = gd.make_desc(C, M, K, 1, 1, dtype, a.layout)
-    plan = gd.gdws_plan(desc, g, W=c2["Wt"])
-    mode = {"auto": gd.MODE_AUTO, "fused": gd.MODE_FUSED, "unfused": gd.MODE_UNFUSED}[a.mode]
-    ws = torch.empty(max(1, gd.gdws_workspace_bytes(plan, N, H, W, mode)), dtype=torch.uint8, device="cuda")
-
+    dense = a.workload == "config2_dense"
+    stream = torch.cuda.Stream()
     x0, x_exact = to_device(c2["X"], dtype, a.layout)
     xs = [x0] + [x0.clone() for _ in range(max(1, a.rotate) - 1)]
     ys = [empty_act(N, M, H, W, dtype, a.layout) for _ in xs]
-    stream = torch.cuda.current_stream()
+    if dense:
+        desc = gd.make_desc(C, M, K, 1, 1, dtype, a.layout)
+        wd, w_exact = to_device(c2["Wt"], dtype, "nchw")
+        ws = torch.empty(max(1, gd.conv_dense_workspace_bytes(desc)), dtype=torch.uint8, device="cuda")
+        G, fused = C * K * K, True
 
-    def step(i):
-        k = i % len(xs)
-        gd.gdws_forward(plan, xs[k], ys[k], N, H, W, workspace=ws, mode=mode, stream=stream)
+        def step(k):
+            gd.conv_dense_forward(desc, wd, xs[k], ys[k], N, H, W, workspace=ws, stream=stream)
+        # eq. 2: the standard convolution's own work and traffic
+        alg_bytes = b * (N * C * H * W + N * M * H * W) + b * M * C * K * K
+        flops = 2.0 * N * H * W * M * C * K * K
+    else:
+        if a.workload == "config2":
+            s, r = gd.gdws_singular_values(c2["Wt"])
+            g = gd.gdws_mego(s, r, gd.gdws_budget_gamma(c2["rho"], C, K, M), g_init=np.ones(C, np.int32), cap=9)
+        else:
+            g = np.full(C, 9 if a.workload == "config2_g9" else 1, np.int32)
+        G = int(g.sum())
+        desc = gd.make_desc(C, M, K, 1, 1, dtype, a.layout)
+        plan = gd.gdws_plan(desc, g, W=c2["Wt"])
+        mode = {"auto": gd.MODE_AUTO, "fused": gd.MODE_FUSED, "unfused": gd.MODE_UNFUSED}[a.mode]
+        ws = torch.empty(max(1, gd.gdws_workspace_bytes(plan, N, H, W, mode)), dtype=torch.uint8, device="cuda")
+        fused = gd.gdws_workspace_bytes(plan, N, H, W, mode) == 0
 
-    clock_ramp(step, a.ramp_ms)
-    for i in range(a.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for i in range(a.steps):
-        step(i)
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall_ms = (t1 - t0) * 1e3 / a.steps
-    dev_ms = ev0.elapsed_time(ev1) / a.steps
+        def step(k):
+            gd.gdws_forward(plan, xs[k], ys[k], N, H, W, workspace=ws, mode=mode, stream=stream)
+        # algorithmic traffic of one launch: read X once, write Y once, read the factors and the tables
+        alg_bytes = b * (N * C * H * W + N * M * H * W) + b * G * (K * K + M) + 4 * (C + 1 + G)
+        flops = 2.0 * N * H * W * G * (K * K + M)
 
-    # algorithmic traffic of one launch: read X once, write Y once, read the factors and the tables
-    alg_bytes = b * (N * C * H * W + N * M * H * W) + b * G * (K * K + M) + 4 * (C + 1 + G)
-    flops = 2.0 * N * H * W * G * (K * K + M)
-    fused = gd.gdws_workspace_bytes(plan, N, H, W, mode) == 0
+    stepper = Stepper(gd, step, len(xs), stream, not a.no_graph)
+    clock_ramp(stepper, a.ramp_ms)
+    wall_ms, dev_ms = timed(stepper, steps, warmup)
+
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    tflops = flops / (dev_ms * 1e-3) / 1e12
+    # which roofline binds: the arithmetic intensity against the ridge of the two peaks (312 FLOP per byte)
+    mfma_bound = flops / alg_bytes > MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    traffic, traffic_src = profile_traffic(a.workload, a.layout) if fused and not dense else (None, None)
+    roof = {"bound": "mfma", "achieved": tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": tflops / MFMA_PEAK_TFLOPS} if mfma_bound else \
+           {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS}
+    roof.update({"traffic": traffic, "traffic_source": traffic_src, "kernel_ms": dev_ms, "tflops": tflops,
+                 "gbs_algorithmic": achieved, "algorithmic_bytes": alg_bytes, "flops": flops,
+                 "measured_copy_rate_gbs": copy_rate_gbs(stream)})
+    what = "standard convolution (conv_dense_forward)" if dense else "GDWS layer"
     out = {
         "metric": "GDWS layer images/sec at batch 256",
         "value": N / (wall_ms * 1e-3),
         "unit": "images/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": wall_ms,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"{a.workload}: GDWS layer bf16 N=256 C=128 16x16 K=3 M=128 G={G}",
+        "config": {"workload": f"{a.workload}: {what} bf16 N=256 C=128 16x16 K=3 M=128 G={G}",
                    "layout": a.layout, "path": "fused" if fused else "unfused (gdw + pw through HBM)",
-                   "rotating_buffers": len(xs), "clock_ramp_ms": a.ramp_ms},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(a.workload, a.layout) if fused else None,
-                     "kernel_ms": dev_ms, "tflops": flops / (dev_ms * 1e-3) / 1e12,
-                     "algorithmic_bytes": alg_bytes},
+                   "rotating_buffers": len(xs), "launch": "eager" if a.no_graph else f"launch graph of {len(xs)} steps",
+                   "clock_ramp_ms": a.ramp_ms, "value_clock": "host wall time", "kernel_ms_clock": "device events"},
+        "roofline": roof,
     }
 
     if not a.no_cpu_baseline:
         import oracle
-        dw, pw = gd.gdws_plan_factors(plan)
-        threads = min(oracle.max_threads(), os.cpu_count() or 1, 16)
+        threads = oracle_threads()
+        if dense:
+            run_oracle = lambda xe, th: oracle.conv_dense(xe, w_exact, stride=1, pad=1, threads=th)
+        else:
+            dw, pw = gd.gdws_plan_factors(plan)
+            run_oracle = lambda xe, th: oracle.gdws_forward(xe, g, dw, pw, stride=1, pad=1, threads=th)
         t0 = time.perf_counter()
-        ref = oracle.gdws_forward(x_exact, g, dw, pw, stride=1, pad=1, threads=threads)
+        ref = run_oracle(x_exact, threads)
         dt1 = time.perf_counter() - t0
         err = rel_l2(from_device(ys[0], dtype, a.layout), ref)
-        reps = max(1, int(round(12.0 / dt1)))            # about 12 s of oracle work in all
+        reps = max(1, int(round(10.0 / dt1)))            # about 10 s of oracle work in all
         t0 = time.perf_counter()
         for _ in range(reps):
-            oracle.gdws_forward(x_exact, g, dw, pw, stride=1, pad=1, threads=threads)
+            run_oracle(x_exact, threads)
         dt = time.perf_counter() - t0
-        n_o = reps * N
-        out["cpu_baseline"] = {"value": n_o / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
+        n1 = max(1, min(N, int(round(N * 3.0 / (dt1 * threads)))))     # about 3 s on one thread
+        t0 = time.perf_counter()
+        run_oracle(x_exact[:n1], 1)
+        d1 = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": reps * N / dt, "unit": "images/s", "cores": threads, "kind": "oracle",
                                "sample": f"the full batch of {N} images, {reps} passes, fp64 direct loops with OpenMP, {dt:.2f} s",
+                               "single_thread": {"value": n1 / d1, "unit": "images/s", "cores": 1,
+                                                 "sample": f"the first {n1} images, one pass, {d1:.2f} s"},
                                "rel_l2_gpu_vs_oracle": err}
     if a.copy_calibration:
         src = torch.empty(a.copy_calibration << 20, dtype=torch.uint8, device="cuda")

@@ -353,12 +353,16 @@ def _run_network(net, shapes, x, dtype, layout):
     return from_device(y, dtype, layout), x_exact
 
 
+NETS = {"vgg16": workloads.vgg16_shape, "resnet18": workloads.resnet18_shape, "resnet50": workloads.resnet50_shape,
+        "wrn28_4": workloads.wrn28_4_shape}
+
+
 @pytest.mark.parametrize("layout", ["nhwc", "nchw"])
 @pytest.mark.parametrize("name,dtype,N,size", [("vgg16", "f16", 2, 32), ("resnet18", "bf16", 2, 32),
-                                                ("resnet50", "bf16", 1, 64), ("vgg16", "f32", 1, 32)])
+                                                ("resnet50", "bf16", 1, 64), ("vgg16", "f32", 1, 32),
+                                                ("wrn28_4", "bf16", 2, 32)])
 def test_network_shapes(name, dtype, N, size, layout):
-    shapes = {"vgg16": workloads.vgg16_shape, "resnet18": workloads.resnet18_shape,
-              "resnet50": workloads.resnet50_shape}[name](size, size)
+    shapes = NETS[name](size, size)
     net, params = _build_network(shapes, dtype, layout)
     x = rng.normal(900, (N, 3, size, size))
     yh, x_exact = _run_network(net, shapes, x, dtype, layout)
@@ -384,13 +388,12 @@ def check_network_output(yh, ref, dtype):
 # the three network workloads at their full batch (the launch configurations the benchmark times: tile sizes, channel
 # slices and buffer reuse depend on the batch); images are independent, so the oracle runs a sample of them alone
 FULL = [("vgg16", "f16", 256, 32, [0, 1, 130, 255]), ("resnet18", "bf16", 512, 32, [0, 255, 256, 511]),
-        ("resnet50", "bf16", 128, 224, [0, 127])]
+        ("resnet50", "bf16", 128, 224, [0, 127]), ("wrn28_4", "bf16", 256, 32, [0, 128, 255])]
 
 
 @pytest.mark.parametrize("name,dtype,N,size,pick", FULL)
 def test_network_full_batch_sampled(name, dtype, N, size, pick):
-    shapes = {"vgg16": workloads.vgg16_shape, "resnet18": workloads.resnet18_shape,
-              "resnet50": workloads.resnet50_shape}[name](size, size)
+    shapes = NETS[name](size, size)
     net, params = _build_network(shapes, dtype, "nhwc")
     x = rng.normal(901, (N, 3, size, size))
     yh, x_exact = _run_network(net, shapes, x, dtype, "nhwc")
@@ -571,8 +574,7 @@ def test_error_paths_on_device():
 
 @pytest.mark.parametrize("name,dtype,size", [("vgg16", "f16", 32), ("resnet18", "bf16", 32), ("resnet50", "bf16", 64)])
 def test_launch_graph_replays_equal_eager(name, dtype, size):
-    shapes = {"vgg16": workloads.vgg16_shape, "resnet18": workloads.resnet18_shape,
-              "resnet50": workloads.resnet50_shape}[name](size, size)
+    shapes = NETS[name](size, size)
     net, params = _build_network(shapes, dtype, "nhwc")
     last = shapes[-1]
     x = rng.normal(905, (1, 3, size, size))

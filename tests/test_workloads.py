@@ -59,5 +59,8 @@ def test_config_shapes():
     r50 = workloads.resnet50_shape()
     assert sum(l.kind == "gdws" for l in r50) == 16
     assert (r50[-1].Ho, r50[-1].M) == (7, 2048)
+    w = workloads.wrn28_4_shape()
+    assert sum(l.kind == "gdws" for l in w) == 25 and sum(l.kind == "dense" for l in w) == 3
+    assert (w[-1].Ho, w[-1].M) == (8, 256) and w[0].M == 16
     g = workloads.skewed_g(77, 64, 201)
     assert g.sum() == 201 and g.min() >= 1 and g.max() <= 9

@@ -204,6 +204,37 @@ def resnet18_shape(H=32, W=32, seed0=31, rho=0.4):
     return _finish(layers, H, W)
 
 
+def wrn28_4_shape(H=32, W=32, seed0=61, rho=0.4):
+    """WideResNet-28-4: 3x3 stem (3 -> 16), three groups of four basic blocks of widths 64 / 128 / 256 (stride 2
+    entering groups 2 and 3), dense 1x1 projection shortcuts where the shape changes: 25 3x3 convolutions, all
+    GDWS on a rho MAC budget with the skewed per-channel draw, plus three 1x1 convolutions.  Same post-activation
+    form with folded batch norm as the ResNet-18 shape."""
+    layers, idx = [], 0
+
+    def gd(C, M, s, src, relu, residual=None):
+        nonlocal idx
+        layers.append(LayerShape("gdws", C, M, 3, s, 1, relu=relu, bias=True, src=src, residual=residual,
+                                 seed=1000 * (seed0 + idx), g_rule=f"skewed:{rho}"))
+        idx += 1
+        return len(layers) - 1
+
+    cur = gd(3, 16, 1, -1, True)
+    c = 16
+    for width, stride in [(64, 1), (128, 2), (256, 2)]:
+        for b in range(4):
+            s = stride if b == 0 else 1
+            if s != 1 or c != width:
+                layers.append(LayerShape("dense", c, width, 1, s, 0, relu=False, bias=True, src=cur,
+                                         seed=1000 * (seed0 + idx) + 500))
+                short = len(layers) - 1
+            else:
+                short = cur
+            a = gd(c, width, s, cur, True)
+            cur = gd(width, width, 1, a, True, residual=short)
+            c = width
+    return _finish(layers, H, W)
+
+
 def resnet50_shape(H=224, W=224, seed0=41):
     """7x7/2 dense stem, 3x3/2 max-pool, bottlenecks [3,4,6,3]; 1x1 convs dense, 3x3 convs GDWS with g_c ~ U{1..9}."""
     layers, idx = [], 0
