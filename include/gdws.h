@@ -199,11 +199,16 @@ int gdws_pw_forward(const gdws_plan_t *plan, const void *t, const void *residual
 
 /* ---- reference point: the standard convolution (eq. 1) ---------------------- */
 
-/* Bytes of device workspace conv_dense_forward needs (a repacked copy of w). */
+/* Bytes of device workspace conv_dense_forward needs: room for a copy of w
+ * repacked in matrix-core operand order where the implicit-GEMM kernel applies
+ * (16-bit storage, NHWC, K = 3, stride 1, pad 1, C a multiple of 16), else 0. */
 size_t conv_dense_workspace_bytes(const gdws_layer_desc_t *desc);
 
 /* y = epilogue(W * x).  w dev [M][C][K][K] in desc->dtype, bias dev fp32 [M]
- * (iff has_bias), residual dev shaped like y (iff has_residual). */
+ * (iff has_bias), residual dev shaped like y (iff has_residual).  Where the
+ * implicit-GEMM kernel applies the call first repacks w into the workspace
+ * (GDWS_EWORKSPACE if it is missing or smaller than conv_dense_workspace_bytes);
+ * every other configuration runs on a direct kernel and needs no workspace. */
 int conv_dense_forward(const gdws_layer_desc_t *desc, const void *w, const float *bias, const void *x,
                        const void *residual, void *y, int32_t N, int32_t H, int32_t W, void *workspace,
                        size_t workspace_bytes, void *stream);

@@ -552,7 +552,10 @@ int gdws_pw_forward(const gdws_plan_t *plan, const void *t, const void *residual
 
 size_t conv_dense_workspace_bytes(const gdws_layer_desc_t *desc)
 {
-    (void)desc;
+    if (check_desc(desc)) return 0;
+    // (the image size is not known here: the kernel's addressing limit is checked by the forward call)
+    if (conv_mfma_supported(desc->dtype, desc->layout, desc->K, desc->stride, desc->pad, desc->C, 0))
+        return conv_mfma_workspace_bytes(desc->C, desc->M);
     return 0;
 }
 
@@ -560,7 +563,6 @@ int conv_dense_forward(const gdws_layer_desc_t *desc, const void *w, const float
                        const void *residual, void *y, int32_t N, int32_t H, int32_t W, void *workspace,
                        size_t workspace_bytes, void *stream)
 {
-    (void)workspace; (void)workspace_bytes;
     int rc = check_desc(desc);
     if (rc) return rc;
     if (!w || !x || !y) return GDWS_ENULL;
@@ -576,6 +578,11 @@ int conv_dense_forward(const gdws_layer_desc_t *desc, const void *w, const float
     a.dtype = desc->dtype; a.layout = desc->layout;
     a.N = N; a.C = desc->C; a.H = H; a.W = W; a.M = desc->M; a.K = desc->K;
     a.stride = desc->stride; a.pad = desc->pad; a.Ho = Ho; a.Wo = Wo;
+    if (conv_mfma_supported(desc->dtype, desc->layout, desc->K, desc->stride, desc->pad, desc->C,
+                            (int64_t)N * desc->C * H * W)) {
+        if (!workspace || workspace_bytes < conv_mfma_workspace_bytes(desc->C, desc->M)) return GDWS_EWORKSPACE;
+        return launch_conv_mfma(a, workspace, (hipStream_t)stream);
+    }
     return launch_dense_direct(a, (hipStream_t)stream);
 }
 
@@ -646,7 +653,9 @@ int layout_buffers(const gdws_net_t *net, int N, int H, int W, NetLayout &lay)
             const NodeShape &r = sh[n.l.residual];
             if (r.C != sh[i].C || r.H != Ho || r.W != Wo) return GDWS_EINVAL;
         }
-        sh[i].scratch = n.l.kind == GDWS_LAYER_GDWS ? gdws_workspace_bytes(n.l.plan, N, ih, iw, GDWS_MODE_AUTO) : 0;
+        sh[i].scratch = n.l.kind == GDWS_LAYER_GDWS    ? gdws_workspace_bytes(n.l.plan, N, ih, iw, GDWS_MODE_AUTO)
+                        : n.l.kind == GDWS_LAYER_DENSE ? conv_dense_workspace_bytes(&n.l.desc)
+                                                       : 0;
         scratch = std::max(scratch, sh[i].scratch);
         if (i == L - 1) { sh[i].offset = SIZE_MAX; break; }
         const size_t need = (sh[i].bytes + 255) & ~(size_t)255;

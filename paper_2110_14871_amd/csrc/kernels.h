@@ -94,6 +94,12 @@ int launch_pw_direct(const PwArgs &a, hipStream_t s);
 int launch_dense_direct(const DenseArgs &a, hipStream_t s);
 int launch_maxpool(const PoolArgs &a, hipStream_t s);
 
+// Standard 3 x 3 convolution as an implicit GEMM on the matrix cores (16-bit NHWC, stride 1, pad 1, C a multiple of 16).
+// The workspace receives the weights repacked in operand order (conv_mfma_workspace_bytes).
+bool conv_mfma_supported(int dtype, int layout, int K, int stride, int pad, int C, int64_t x_elems);
+size_t conv_mfma_workspace_bytes(int C, int M);
+int launch_conv_mfma(const DenseArgs &a, void *workspace, hipStream_t s);
+
 // Fused GDWS forward on the vector ALUs for the shapes the matrix-core kernel does not take (any dtype / layout / K).
 struct FusedGenericArgs {
     const void *x;

@@ -312,7 +312,10 @@ def test_random_shapes(block):
 # reference point, pooling, networks, error paths
 # ------------------------------------------------------------------------------------------
 
-DENSE = [(2, 16, 12, 12, 24, 3, 1, 1), (2, 3, 20, 20, 16, 7, 2, 3), (3, 32, 8, 8, 48, 1, 2, 0), (1, 8, 9, 7, 8, 3, 2, 1)]
+DENSE = [(2, 16, 12, 12, 24, 3, 1, 1), (2, 3, 20, 20, 16, 7, 2, 3), (3, 32, 8, 8, 48, 1, 2, 0), (1, 8, 9, 7, 8, 3, 2, 1),
+         # 3 x 3, stride 1, C a multiple of 16: the implicit GEMM on the matrix cores (16-bit NHWC); several tiles per
+         # image, a last chunk of 16 channels, two slices of output channels with a ragged end, images narrower than a tile
+         (3, 128, 16, 16, 128, 3, 1, 1), (2, 80, 19, 37, 72, 3, 1, 1), (1, 32, 5, 7, 200, 3, 1, 1), (2, 144, 33, 8, 36, 3, 1, 1)]
 
 
 @pytest.mark.parametrize("layout", ["nhwc", "nchw"])
