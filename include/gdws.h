@@ -75,6 +75,22 @@ const char *gdws_strerror(int code);
  * NULL) = number of sigma above max(M,K^2) * eps * sigma_1. */
 int gdws_singular_values(const float *W, int32_t M, int32_t C, int32_t K, double *sigma, int32_t *rank);
 
+/* The same singular values computed on the device, for a weight that already
+ * lives there (the ranking step of Algorithms 1 and 2 over all layers of a
+ * network without a round trip to the host).  One wave per channel forms the
+ * K^2 x K^2 Gram matrix W_c^T W_c in fp64 and diagonalises it with cyclic
+ * Jacobi rotations.  w_dev device fp32 [M][C][K][K]; sigma_dev device fp64
+ * [C][R] out, R = min(M, K^2), descending; rank_dev device int32 [C] out or NULL
+ * = number of sigma_i^2 above 64 * max(M,K^2) * eps * sigma_1^2 (the Gram matrix
+ * resolves singular values down to about sqrt(eps) sigma_1 only, so the
+ * threshold is coarser than the host routine's); v_dev device fp64
+ * [C][R][K^2] out or NULL = right singular vectors v_i (Lemma 3's depthwise
+ * filters), each with its largest-magnitude entry (first on ties) positive.
+ * Asynchronous on `stream`; allocates nothing.  GDWS_EUNSUPPORTED for K > 7,
+ * GDWS_EINVAL for sizes below 1, GDWS_ENULL for a missing w_dev or sigma_dev. */
+int gdws_singular_values_device(const float *w_dev, int32_t M, int32_t C, int32_t K, double *sigma_dev,
+                                int32_t *rank_dev, double *v_dev, void *stream);
+
 /* Algorithm 1 (MEGO): greedy channel distribution vector minimising the weighted
  * error of eq. 4 subject to sum(g) <= gamma.  sigma host [C][R] and rank host [C]
  * as returned above; alpha host [C] or NULL (all ones); g host [C] in/out: on entry

@@ -50,6 +50,7 @@ def lib():
         sig = {
             "gdws_strerror": (ctypes.c_char_p, [ctypes.c_int]),
             "gdws_singular_values": (ctypes.c_int, [vp, i32, i32, i32, vp, vp]),
+            "gdws_singular_values_device": (ctypes.c_int, [vp, i32, i32, i32, vp, vp, vp, vp]),
             "gdws_mego": (ctypes.c_int, [vp, vp, i32, i32, vp, i64, i32, vp]),
             "gdws_lego": (ctypes.c_int, [vp, vp, i32, i32, vp, dbl, i32, i32, vp]),
             "gdws_budget_gamma": (i64, [dbl, i32, i32, i32]),
@@ -85,7 +86,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_mego", "gdws_lego", "gdws_budget_gamma",
+EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_singular_values_device", "gdws_mego", "gdws_lego", "gdws_budget_gamma",
            "gdws_compact_factors", "gdws_plan_sparse", "gdws_plan", "gdws_plan_destroy",
            "gdws_plan_info", "gdws_plan_factors", "gdws_intermediate_channels", "gdws_workspace_bytes", "gdws_forward",
            "gdws_forward_maxpool2", "gdws_forward_static", "gdws_gdw_forward",
@@ -141,6 +142,13 @@ def gdws_singular_values(W):
     _check(lib().gdws_singular_values(wp, M, C, K, sigma.ctypes.data_as(ctypes.c_void_p),
                                       rank.ctypes.data_as(ctypes.c_void_p)), "gdws_singular_values")
     return sigma, rank
+
+
+def gdws_singular_values_device(w, sigma, rank=None, v=None, stream=None):
+    """Device version: w float32 [M, C, K, K], sigma float64 [C, R], rank int32 [C], v float64 [C, R, K*K], all GPU tensors."""
+    M, C, K, _ = w.shape
+    _check(lib().gdws_singular_values_device(_dev(w), M, C, K, _dev(sigma), _dev(rank), _dev(v), _stream(stream)),
+           "gdws_singular_values_device")
 
 
 def gdws_mego(sigma, rank, gamma, alpha=None, g_init=None, cap=0):

@@ -290,6 +290,14 @@ int gdws_singular_values(const float *W, int32_t M, int32_t C, int32_t K, double
     GDWS_CATCH
 }
 
+int gdws_singular_values_device(const float *w_dev, int32_t M, int32_t C, int32_t K, double *sigma_dev,
+                                int32_t *rank_dev, double *v_dev, void *stream)
+{
+    if (!w_dev || !sigma_dev) return GDWS_ENULL;
+    if (M < 1 || C < 1 || K < 1) return GDWS_EINVAL;
+    return launch_svd_device(w_dev, M, C, K, sigma_dev, rank_dev, v_dev, (hipStream_t)stream);
+}
+
 int gdws_mego(const double *sigma, const int32_t *rank, int32_t C, int32_t R, const double *alpha, int64_t gamma,
               int32_t cap, int32_t *g)
 {

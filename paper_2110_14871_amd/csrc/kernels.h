@@ -100,6 +100,10 @@ bool conv_mfma_supported(int dtype, int layout, int K, int stride, int pad, int 
 size_t conv_mfma_workspace_bytes(int C, int M);
 int launch_conv_mfma(const DenseArgs &a, void *workspace, hipStream_t s);
 
+// Singular values (descending), numerical rank and, optionally, right singular vectors of the C slices W_c (M x K^2)
+// of a weight [M][C][K][K] in device memory: one wave per slice, Jacobi on the Gram matrix in fp64.  K <= 7.
+int launch_svd_device(const float *w, int M, int C, int K, double *sigma, int32_t *rank, double *v, hipStream_t s);
+
 // Fused GDWS forward on the vector ALUs for the shapes the matrix-core kernel does not take (any dtype / layout / K).
 struct FusedGenericArgs {
     const void *x;

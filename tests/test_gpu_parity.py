@@ -167,6 +167,7 @@ SWEEP = [
     (2, 32, 16, 16, 64, 3, 2, 1, "u14"),     # stride 2
     (2, 8, 15, 15, 16, 3, 2, 1, "u13"),      # stride 2, odd
     (1, 6, 9, 9, 12, 5, 1, 2, "u13"),        # K = 5
+    (2, 4, 19, 18, 24, 7, 2, 3, "u14"),      # K = 7, stride 2, pad 3 (an ImageNet stem's geometry)
     (2, 10, 8, 8, 7, 1, 1, 0, "u13"),        # K = 1
     (2, 12, 12, 12, 20, 3, 1, 0, "u13"),     # no padding
     (5, 64, 4, 4, 128, 3, 1, 1, "u14"),      # tiny images, many channels
@@ -658,3 +659,59 @@ def test_sparse_aware_plan(M, C, keep, dtype, layout, mode):
     # the layer is the pruned standard convolution itself, up to the rounding of the factors (Lemma 1)
     dense = oracle.conv_dense(x_exact, Wq, stride=1, pad=1)
     assert rel_l2(outs[1], dense) <= (1e-5 if dtype == "f32" else 2e-2)
+
+
+# ------------------------------------------------------------------------------------------
+# batched singular values on the device (the ranking step of Algorithms 1 and 2)
+# ------------------------------------------------------------------------------------------
+
+SVD_CASES = [
+    # M, C, K, std, note
+    (128, 128, 3),     # config 2's weight
+    (12, 6, 5),        # K = 5
+    (4, 10, 3),        # fewer rows than taps: R = M
+    (64, 3, 7),        # a 7 x 7 stem: K^2 = 49 < M
+    (1, 5, 1),         # 1 x 1, one output channel
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", range(len(SVD_CASES)))
+def test_singular_values_device(case):
+    """sigma, rank and V from the device routine against the oracle's SVD (numpy) of the same slices."""
+    M, C, K = SVD_CASES[case]
+    KK, R = K * K, min(M, K * K)
+    W = rng.normal(9100 + case, (M, C, K, K), std=0.05)
+    if C > 2:
+        W[:, 2] = 0.0                                    # a zero slice: rank 0
+    if C > 3 and M > 2 and KK > 2:
+        W[:, 3] = np.outer(W[:, 3, 0, 0], W[0, 3].reshape(-1)).reshape(M, K, K)   # a rank-1 slice
+    w = torch.from_numpy(W).cuda()
+    sigma = torch.full((C, R), float("nan"), dtype=torch.float64, device="cuda")
+    rank = torch.full((C,), -1, dtype=torch.int32, device="cuda")
+    v = torch.full((C, R, KK), float("nan"), dtype=torch.float64, device="cuda")
+    gd.gdws_singular_values_device(w, sigma, rank, v)
+    torch.cuda.synchronize()
+    sigma, rank, v = sigma.cpu().numpy(), rank.cpu().numpy(), v.cpu().numpy()
+    U, S, Vt = oracle.svd_slices(W.astype(np.float64))
+    s1 = max(S.max(), 1e-300)
+    # the Gram matrix resolves sigma to eps * sigma_1^2 / sigma; relative to sigma_1 the error is below sqrt(eps)
+    assert np.max(np.abs(sigma - S)) <= 2e-8 * s1
+    big = S > 1e-3 * s1
+    assert np.max(np.abs(sigma - S)[big]) <= 1e-11 * s1
+    # (the device routine's rank rule, on squares: see the header) applied to the oracle's singular values
+    ref_rank = (S ** 2 > 64 * max(M, KK) * np.finfo(np.float64).eps * S[:, :1] ** 2).sum(axis=1)
+    assert np.array_equal(rank, ref_rank), (rank, ref_rank)
+    Wc = oracle.slices(W.astype(np.float64))                          # [C, M, KK]
+    for c in range(C):
+        r = int(ref_rank[c])
+        Vc = v[c]                                                      # rows: v_i
+        assert np.allclose(Vc @ Vc.T, np.eye(R), atol=1e-12)          # orthonormal (also inside a null space)
+        G = Wc[c].T @ Wc[c]
+        assert np.allclose(Vc @ G @ Vc.T, np.diag(sigma[c] ** 2), atol=1e-12 * max(s1 * s1, 1e-300))
+        for i in range(r):                                             # sign convention, and the oracle's vectors
+            k = int(np.argmax(np.abs(Vc[i])))
+            assert Vc[i, k] > 0
+            gap = min([abs(S[c, i] - S[c, j]) for j in range(R) if j != i] + [S[c, i]])
+            if gap > 1e-6 * s1:
+                assert np.allclose(Vc[i], Vt[c, i], atol=1e-7 * s1 / gap)
