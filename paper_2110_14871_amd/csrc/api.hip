@@ -37,6 +37,7 @@ struct gdws_plan_s {
     float *d_bias = nullptr;  // [M]
     FusedSchedule fused;      // tables of the fused kernel (valid only for the shapes it covers)
     FusedSchedule gdwm;       // tables of its depthwise-only mode (16-bit NHWC, single-stage layers)
+    FusedSchedule deep;       // tables of the deep-layer fused kernel (16-bit NHWC, 128 < C <= 512, M >= 256)
     PwMfmaTables pwm;         // tables of the MFMA pointwise kernel (16-bit NHWC)
     DenseMfmaTables gdm;      // depthwise stage of a 3-channel layer as an implicit GEMM (16-bit NHWC)
     GdwLdsTables gdl;         // tables of the LDS-tiled depthwise kernel (16-bit NHWC, K = 3)
@@ -48,6 +49,8 @@ struct gdws_plan_s {
         (void)hipFree(fused.d_stage_tab); (void)hipFree(fused.d_records);
         (void)hipFree(fused.d_pwfrag); (void)hipFree(fused.d_bias_pad);
         (void)hipFree(gdwm.d_stage_tab); (void)hipFree(gdwm.d_records); (void)hipFree(gdwm.d_bias_pad);
+        (void)hipFree(deep.d_stage_tab); (void)hipFree(deep.d_records); (void)hipFree(deep.d_pwfrag);
+        (void)hipFree(deep.d_bias_pad);
         (void)hipFree(pwm.d_frag); (void)hipFree(pwm.d_bias_pad); (void)hipFree(gdl.d_chunks);
         (void)hipFree(gdm.d_frag); (void)hipFree(gdm.d_bias_pad);
     }
@@ -226,6 +229,9 @@ bool fused_supported(const gdws_plan_t *p, int N, int H, int W)
                                                    (int64_t)N * d.C * H * W);
 }
 
+constexpr int64_t kDeepMinWorkgroups = 64;
+constexpr int64_t kDeepMaxPixels = 16384;  // output pixels of the batch above which the general kernel's tiles fill the chip
+
 int run_fused(const gdws_plan_t *p, const void *x, const void *residual, void *y, int N, int H, int W, int Ho, int Wo,
               hipStream_t s, int pool = 0)
 {
@@ -234,6 +240,15 @@ int run_fused(const gdws_plan_t *p, const void *x, const void *residual, void *y
     a.x = x; a.y = y; a.ep = plan_epilogue(p, residual); a.sched = &p->fused;
     a.dtype = p->desc.dtype; a.layout = p->desc.layout; a.stride = p->desc.stride;
     a.N = N; a.C = p->desc.C; a.H = H; a.W = W; a.M = p->desc.M; a.Ho = Ho; a.Wo = Wo;
+    // Few pixels and many channels: the kernel whose waves split the output channels of one 32-pixel block, when its
+    // grid gives the chip enough workgroups.
+    if (deep_workgroups(p->deep, N, a.C, H, W, a.M, Ho, Wo, pool != 0) >= kDeepMinWorkgroups &&
+        (int64_t)N * Ho * Wo <= kDeepMaxPixels && !(pool && a.ep.residual)) {
+        FusedArgs d = a;
+        d.sched = &p->deep;
+        const int rc = launch_fused_deep(d, s);
+        if (rc != GDWS_EUNSUPPORTED) return rc;
+    }
     return launch_fused(a, s);
 }
 
@@ -411,6 +426,15 @@ int plan_impl(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, c
         if (!rc) rc = upload(&p->fused.d_records, p->fused.records);
         if (!rc) rc = upload(&p->fused.d_pwfrag, p->fused.pwfrag);
         if (!rc) rc = upload(&p->fused.d_bias_pad, p->fused.bias_pad);
+    }
+    if (!rc && deep_shape_supported(desc->dtype, desc->layout, desc->K, desc->stride, desc->pad, C, M)) {
+        build_fused_schedule(p->deep, desc->dtype, desc->stride, C, M, g, p->offsets.data(), p->dw.data(),
+                             p->pw.data(), desc->has_bias ? p->bias.data() : nullptr, false, C <= 256 ? 256 : 512);
+        if (p->deep.valid) {
+            rc = upload(&p->deep.d_records, p->deep.records);
+            if (!rc) rc = upload(&p->deep.d_pwfrag, p->deep.pwfrag);
+            if (!rc) rc = upload(&p->deep.d_bias_pad, p->deep.bias_pad);
+        }
     }
     p->Gt = G;
     if (!rc && desc->layout == GDWS_NHWC && desc->dtype != GDWS_F32) {

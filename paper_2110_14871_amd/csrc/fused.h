@@ -53,6 +53,7 @@ struct FusedSchedule {
     int m_blocks = 0;        // ceil(M / 32)
     int mb_per_wg = 0;       // 32-wide blocks of M per workgroup (2 or 4)
     int m_blocks_pad = 0;    // m_blocks rounded up to a multiple of mb_per_wg
+    int record_slots = 0;    // row-block records stored: n_rowblocks plus the all-zero ones the kernels read ahead into
     std::vector<int32_t> stage_tab;  // per non-empty stage: c_begin, c_count
     // (n_rowblocks + 2) x 64 lanes x 4 dwords, then (n_rowblocks + 2) x 64 lanes x 2 dwords (two row blocks of
     // zeros at the end: the records are read two row blocks ahead)
@@ -67,9 +68,12 @@ struct FusedSchedule {
 };
 
 // Builds the host tables from the (already rounded) factors.  dw [G][9], pw [M][G], bias [M] or nullptr.
+// deep_stage (0, 256 or 512): the schedule of the deep-layer kernel (kernels_fused_deep.hip) -- all input channels
+// are one stage of that many channels, the row blocks are padded with empty ones to a multiple of four and the
+// output channels to a multiple of 256.
 void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M, const int32_t *g,
                           const int32_t *offsets, const float *dw, const float *pw, const float *bias,
-                          bool gdw_only = false);
+                          bool gdw_only = false, int deep_stage = 0);
 
 struct FusedArgs {
     const void *x;
@@ -88,5 +92,10 @@ bool fused_shape_supported(int dtype, int layout, int K, int stride, int pad, in
 bool fused_image_supported(const FusedSchedule &s, int layout, int stride, int C, int Ho, int Wo, bool residual,
                            int64_t x_elems);
 int launch_fused(const FusedArgs &a, hipStream_t s);
+
+// The deep-layer kernel: few pixels, many channels (see kernels_fused_deep.hip).  a.sched is a deep schedule.
+bool deep_shape_supported(int dtype, int layout, int K, int stride, int pad, int C, int M);
+int64_t deep_workgroups(const FusedSchedule &sc, int N, int C, int H, int W, int M, int Ho, int Wo, bool pool);
+int launch_fused_deep(const FusedArgs &a, hipStream_t s);
 
 }  // namespace gdws

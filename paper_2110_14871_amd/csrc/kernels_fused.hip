@@ -97,20 +97,21 @@ TileChoice choose_tile(int Ho, int Wo, int stride, int C, int mb, bool nhwc, boo
 }  // namespace
 
 void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M, const int32_t *g,
-                          const int32_t *offsets, const float *dw, const float *pw, const float *bias, bool gdw_only)
+                          const int32_t *offsets, const float *dw, const float *pw, const float *bias, bool gdw_only,
+                          int deep_stage)
 {
     (void)g;
     const int G = offsets[C];
     s = FusedSchedule{};
     s.gdw_only = gdw_only;
-    const StageGeometry sg = stage_geometry(stride, C);
+    const StageGeometry sg = deep_stage ? StageGeometry{false, deep_stage, 32, 1} : stage_geometry(stride, C);
     s.stride = stride;
     s.big = sg.big;
     s.stage_channels = sg.stage_channels;
     s.chunk_channels = sg.chunk_channels;
     s.buffers = sg.buffers;
     s.m_blocks = (M + 31) / 32;
-    s.mb_per_wg = s.m_blocks >= 3 ? 4 : 2;
+    s.mb_per_wg = deep_stage ? 8 : s.m_blocks >= 3 ? 4 : 2;
     s.m_blocks_pad = (s.m_blocks + s.mb_per_wg - 1) / s.mb_per_wg * s.mb_per_wg;
     s.bias_pad.assign((size_t)s.m_blocks_pad * 32, 0.f);
     if (bias) std::copy(bias, bias + M, s.bias_pad.begin());
@@ -193,8 +194,16 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
         chunk_base += (cfill + s.chunk_channels - 1) / s.chunk_channels;
     }
     s.n_chunks = chunk_base;
+    while (deep_stage && !rbs.empty() && rbs.size() % 4) {  // empty row blocks: no rows, no weights
+        RowBlock rb{};
+        for (int r = 0; r < kRowBlock; ++r) rb.rows[r] = -1;
+        rbs.push_back(rb);
+    }
     s.n_rowblocks = (int)rbs.size();
-    const size_t slots = rbs.size() + 2;
+    // all-zero records behind the last row block: the general kernel reads two row blocks ahead, the deep-layer
+    // kernel two groups of four
+    const size_t slots = rbs.size() + (deep_stage ? 8 : 2);
+    s.record_slots = (int)slots;
     s.records.assign(slots * 64 * 6, 0u);
     uint32_t *rec_a = s.records.data(), *rec_b = s.records.data() + slots * 64 * 4;
     int passed = 0;  // chunk barriers the compute waves have executed so far
@@ -232,7 +241,7 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
         push_fragments(rb.rows);
     }
     s.final_waits = s.n_chunks - passed;
-    push_fragments(nullptr);  // read ahead by one row block
+    for (int k = 0; k < (deep_stage ? 4 : 1); ++k) push_fragments(nullptr);  // read ahead by one row block (one group)
 }
 
 bool fused_shape_supported(int dtype, int layout, int K, int stride, int pad, int C, int M)
@@ -312,9 +321,8 @@ int launch_fused(const FusedArgs &a, hipStream_t s)
     p.x = (const uint16_t *)a.x; p.y = (uint16_t *)a.y;
     p.residual = (const uint16_t *)a.ep.residual; p.bias = sc.d_bias_pad;
     p.stage_tab = sc.d_stage_tab;
-    const size_t slots = (size_t)sc.n_rowblocks + 2;
     p.rec_a = (const u32x4_t *)sc.d_records;
-    p.rec_b = (const u32x2_t *)(sc.d_records + slots * 64 * 4);
+    p.rec_b = (const u32x2_t *)(sc.d_records + (size_t)sc.record_slots * 64 * 4);
     p.pwfrag = (const u32x4_t *)sc.d_pwfrag;
     p.n_stages = sc.n_stages; p.n_rowblocks = sc.n_rowblocks; p.final_waits = sc.final_waits;
     p.m_blocks_pad = sc.m_blocks_pad; p.relu = a.ep.relu;

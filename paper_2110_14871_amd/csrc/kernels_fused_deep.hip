@@ -1,0 +1,411 @@
+// Fused GDWS kernel for the deep layers of a network: few pixels, many input and output channels
+// (K = 3, stride 1, pad 1, 16-bit NHWC, 128 < C <= 512, M >= 256).
+//
+// On such layers the general fused kernel (fused_kernel.h) has to cut the output channels into slices of 64 to get
+// a workgroup per CU, and every slice repeats the depthwise stage of the tile, which is most of a row block's
+// instructions.  Here the four waves of a workgroup share ONE block of 32 output pixels and split the output
+// channels instead (64 each, 256 per workgroup): the row blocks are taken four at a time, wave w computes the
+// depthwise stage of row block 4 k + w for the 32 pixels (nine MFMAs, as in the general kernel: sparse A from the
+// row block's record, B a 16-byte LDS read of the input tile, the middle tap of a filter row from the neighbouring
+// lanes), rounds the 32 x 32 result and puts it into LDS in the layout the pointwise MFMA wants for its B operand
+// (16 bytes per lane and K-step: conflict-free to write and to read); after a barrier every wave runs the
+// pointwise MFMAs of all four row blocks against its own 64 output channels.  The depthwise work of a tile is thus
+// done once per 256 output channels, and a wave issues 25 MFMAs per group of four row blocks where the general
+// kernel's 64-channel slices issue 52.
+//
+// The whole input tile (32 pixels with halo, all C channels, pixel-major, 16 bytes of padding per pixel) is loaded
+// into LDS by the four waves before the first row block: one stage, no loader waves.  Records, pointwise
+// fragments and bias are the general kernel's (build_fused_schedule with its deep_stage argument: one stage, the
+// row blocks padded to a multiple of four, the output channels to a multiple of 256).
+#include <algorithm>
+
+#include "fused_kernel.h"
+
+namespace gdws {
+
+using namespace fusedk;
+
+namespace {
+
+constexpr int kDeepThreads = 256;
+constexpr int kDeepPx = 32;                  // output pixels per workgroup
+constexpr int kDeepMbWave = 2;               // 32-wide blocks of output channels per wave
+constexpr int kDeepMbWg = 4 * kDeepMbWave;   // per workgroup: 256 channels
+constexpr int kDeepMaxLds = 160 * 1024;
+constexpr int kTSlotDwords = 2 * 4 * 2 * 64 * 4;  // two buffers x four row blocks x two K-steps x 64 lanes x 16 bytes
+
+struct DeepParams {
+    const uint16_t *x;
+    uint16_t *y;
+    const uint16_t *residual;
+    const float *bias;
+    const u32x4_t *rec_a;
+    const u32x2_t *rec_b;
+    const u32x4_t *pwfrag;
+    int n_groups;  // row blocks / 4
+    int m_blocks_pad, relu;
+    int N, C, H, W, M, Ho, Wo;
+    int TH, TN, IH, th_log2;
+    uint32_t x_bytes;
+    int tiles_x, tiles_y;
+    int tslot_off;  // dword offset in LDS of the intermediate's slots (behind the input tile)
+    int pool, Hp, Wp;
+};
+
+// CS: channels the LDS tile holds per pixel (256 or 512).
+template <int DTYPE, int TW, int CS>
+__global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams params)
+{
+    using Op = half_ops<DTYPE>;
+    const DeepParams &p = params;
+    constexpr int PSW = CS / 2 + 4;  // dwords per LDS pixel
+    constexpr int IW = TW + 2;
+    constexpr int QP = CS / 8;       // 16-byte pieces per pixel
+    extern __shared__ uint32_t lds[];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, lhi = lane >> 5;
+    int tile = blockIdx.x;
+    const int tx0 = (tile % p.tiles_x) * TW; tile /= p.tiles_x;
+    const int ty0 = (tile % p.tiles_y) * p.TH;
+    const int n0 = (tile / p.tiles_y) * p.TN;
+    const int mslice = blockIdx.y;                                // 256 output channels
+    const int mb0 = mslice * kDeepMbWg + wave * kDeepMbWave;      // the wave's first 32-wide block of them
+
+    // ---- records and pointwise fragments of the first group: requested before anything else ----
+    u32x4_t ra = p.rec_a[wave * 64 + lane], na = p.rec_a[(4 + wave) * 64 + lane];
+    u32x2_t rb = p.rec_b[wave * 64 + lane], nb = p.rec_b[(4 + wave) * 64 + lane];
+    const int kstep_stride = p.m_blocks_pad * 64;          // 16-byte units per K-step of a row block
+    const u32x4_t *fp = p.pwfrag + (int64_t)mb0 * 64 + lane;  // (row block 0, K-step 0, the wave's blocks)
+    u32x4_t pwf[4][2][kDeepMbWave];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int mb = 0; mb < kDeepMbWave; ++mb) pwf[s][s2][mb] = fp[(s * 2 + s2) * kstep_stride + mb * 64];
+
+    // ---- the input tile: 16-byte pieces, consecutive threads along a pixel's channels ----
+    {
+        const int npix = p.TN * p.IH * IW;
+        const int total = npix * QP;
+        constexpr uint32_t kOutside = 0x80000000u;  // beyond the descriptor's bound: the load returns zeros
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, 0x00020000);
+        constexpr int kStepPix = kDeepThreads / QP;  // pixels from one of a thread's pieces to its next (4 or 8)
+        constexpr int kStepX = kStepPix % IW, kStepY = kStepPix / IW;
+        static_assert(kStepY <= 1, "the walk over the tile's pixels advances by less than two rows per step");
+        const int q = threadIdx.x % QP;
+        int pix = threadIdx.x / QP;
+        int ix = pix % IW, iy, tn;
+        {
+            const int r = pix / IW;
+            iy = r % p.IH; tn = r / p.IH;
+        }
+        const int gy0 = ty0 - 1, gx0 = tx0 - 1;
+        const uint32_t c2 = (uint32_t)p.C * 2u;
+        const bool chan_in = q * 8 < p.C;
+        constexpr int kBatch = 8;
+        for (int i0 = threadIdx.x; i0 < total; i0 += kDeepThreads * kBatch) {
+            u32x4_t v[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int n = n0 + tn, gy = gy0 + iy, gx = gx0 + ix;
+                const bool in = chan_in && tn < p.TN && n < p.N && (unsigned)gy < (unsigned)p.H && (unsigned)gx < (unsigned)p.W;
+                // 24-bit multiplies: the host admits fewer than 2^24 input pixels and x below 2 GiB
+                const uint32_t pixel = __umul24(__umul24(n, p.H) + gy, p.W) + gx;
+                const uint32_t off = in ? __umul24(pixel, c2) + q * 16 : kOutside;
+                v[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+                ix += kStepX; iy += kStepY;
+                if (ix >= IW) { ix -= IW; ++iy; }
+                if (iy >= p.IH) { iy -= p.IH; ++tn; }  // (IH >= 3 > the two rows a step can add)
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int i = i0 + kDeepThreads * k;
+                if (i < total) *(u32x4_t *)(lds + (pix + kStepPix * k) * PSW + q * 4) = v[k];
+            }
+            pix += kStepPix * kBatch;
+        }
+    }
+    __syncthreads();
+
+    // ---- compute ----
+    // LDS dword offset of the top-left tap of the lane's pixel, plus the lane's half of the 16-channel window
+    int base;
+    {
+        const int tx = l32 % TW, ty = (l32 / TW) & (p.TH - 1), tn = (l32 / TW) >> p.th_log2;
+        base = ((tn * p.IH + ty) * IW + tx) * PSW + lhi * 4;
+    }
+    // accumulators start from the bias: D[m][pixel], register i <-> channel 8 * (i / 4) + 4 * lhi + i % 4
+    f32x16_t acc[kDeepMbWave];
+#pragma unroll
+    for (int mb = 0; mb < kDeepMbWave; ++mb) {
+        const float *bp = p.bias + (mb0 + mb) * 32;  // padded with zeros to whole blocks
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4_t bv = *(const f32x4_t *)(bp + 8 * q4 + 4 * lhi);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[mb][4 * q4 + i] = bv[i];
+        }
+    }
+    f32x16_t zero;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+    uint32_t *tslots = lds + p.tslot_off;
+
+    auto tap_offset = [](int tap) { return ((tap / 3) * IW + (tap % 3)) * PSW; };
+    auto read16 = [](const uint32_t *ptr) { return *(const u32x4_a8_t *)ptr; };
+    // the six operands that come from LDS: left and right tap of each filter row
+    u32x4_t bq[6];
+    auto read_operands = [&](uint32_t ctrl) {
+        const uint32_t *src = lds + base + (ctrl & 0xff);
+#pragma unroll
+        for (int i = 0; i < 6; ++i) bq[i] = read16(src + tap_offset(3 * (i / 2) + 2 * (i % 2)));
+    };
+    read_operands((uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]));
+
+    for (int gi = 0; gi < p.n_groups; ++gi) {
+        // ---- depthwise stage of row block 4 gi + wave ----
+        const uint32_t sel = rb[0] >> 16;
+        const uint32_t hm = (sel & 8) ? 0xFFFF0000u : 0x0000FFFFu;
+        uint32_t m[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) m[d] = (sel & 7) == (uint32_t)d ? hm : 0u;
+        auto a_operand = [&](int tap) {
+            const uint32_t word = tap == 8 ? rb[0] : ra[tap / 2];
+            const uint32_t dup = __builtin_amdgcn_perm(word, word, (tap & 1) ? 0x03020302u : 0x01000100u);
+            return u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
+        };
+        // two accumulation chains (the middle taps apart) so that consecutive MFMAs do not wait for each other
+        f32x16_t t = zero, tm = zero;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const u32x4_t &bl = bq[2 * u], &br = bq[2 * u + 1];
+            t = Op::mfma(a_operand(3 * u), bl, t);
+            u32x4_t mid;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                if constexpr (TW >= 8) {
+                    // lanes 0-3 and 8-11 of a 16-lane row take the left tap of the next pixel, the others the
+                    // right tap of the previous one: no lane reaches across the end of an 8-pixel tile row
+                    const uint32_t x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bl[d], 0x101, 0xf, 0xf, true);
+                    mid[d] = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)br[d], 0x111, 0xf, 0xa, false);
+                } else {
+                    // four-pixel tile rows are the quads
+                    const uint32_t nx = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)bl[d], 0xE9, 0xf, 0xf, false);
+                    const uint32_t pv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)br[d], 0x90, 0xf, 0xf, false);
+                    mid[d] = (lane & 2) ? pv : nx;
+                }
+            }
+            tm = Op::mfma(a_operand(3 * u + 1), mid, tm);
+            t = Op::mfma(a_operand(3 * u + 2), br, t);
+        }
+        // rounded to the storage type; register i of a lane is K element i % 8 of K-step i / 8 of the pointwise MFMA
+        uint32_t *slot = tslots + ((gi & 1) * 4 + wave) * (2 * 64 * 4) + lane * 4;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            u32x4_t tb;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                tb[d] = Op::pack(t[8 * s2 + 2 * d] + tm[8 * s2 + 2 * d], t[8 * s2 + 2 * d + 1] + tm[8 * s2 + 2 * d + 1]);
+            *(u32x4_t *)(slot + s2 * (64 * 4)) = tb;
+        }
+        // the next group's record becomes the current one; the one after it is requested
+        {
+            const uint32_t ri = (uint32_t)((gi + 2) * 4 + wave) * 64u + (uint32_t)lane;
+            ra = na; rb = nb;
+            na = p.rec_a[ri]; nb = p.rec_b[ri];
+        }
+        __syncthreads();  // the four row blocks of the group are in LDS
+        // the next group's operands are requested now: they arrive during the pointwise MFMAs
+        read_operands((uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]));
+        // ---- pointwise stage: four row blocks x two K-steps against the wave's 64 output channels ----
+        fp += 8 * kstep_stride;  // the next group's fragments
+        const uint32_t *tsrc = tslots + (gi & 1) * 4 * (2 * 64 * 4) + lane * 4;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const u32x4_t b = *(const u32x4_t *)(tsrc + (s * 2 + s2) * (64 * 4));
+#pragma unroll
+                for (int mb = 0; mb < kDeepMbWave; ++mb) {
+                    acc[mb] = Op::mfma(pwf[s][s2][mb], b, acc[mb]);
+                    pwf[s][s2][mb] = fp[(s * 2 + s2) * kstep_stride + mb * 64];
+                }
+            }
+    }
+    __syncthreads();  // every wave is done with the input tile and the slots: the output tile may overwrite them
+
+    // ---- epilogue, part 1: residual, ReLU, rounding in registers; the tile goes to LDS ----
+    constexpr int kRowHalfs = kDeepMbWg * 32 + 8;  // [32 pixels][256 channels], rows padded by 16 bytes
+    uint16_t *tile16 = (uint16_t *)lds;
+    int *pixtab = (int *)(tile16 + kDeepPx * kRowHalfs);
+    int my_pix;
+    {
+        const int row = l32 / TW;
+        const int ox = tx0 + (l32 & (TW - 1)), oy = ty0 + (row & (p.TH - 1)), on = n0 + (row >> p.th_log2);
+        my_pix = (on < p.N && oy < p.Ho && ox < p.Wo) ? (on * p.Ho + oy) * p.Wo + ox : -1;
+        if (wave == 0 && lhi == 0) pixtab[l32] = my_pix;
+    }
+#pragma unroll
+    for (int mb = 0; mb < kDeepMbWave; ++mb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int col = (wave * kDeepMbWave + mb) * 32 + 8 * q4 + 4 * lhi;  // four consecutive output channels
+            const int mch = mslice * (kDeepMbWg * 32) + col;
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = acc[mb][4 * q4 + i];
+            if (p.residual && my_pix >= 0 && mch < p.M) {  // (M is a multiple of 8: the four channels are inside together)
+                const u32x2_t r = *(const u32x2_t *)(p.residual + (int64_t)my_pix * p.M + mch);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] += Op::widen((uint16_t)(r[i / 2] >> (16 * (i & 1))));
+            }
+            if (p.relu) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = relu_bits(v[i]);
+            }
+            *(u32x2_t *)(tile16 + l32 * kRowHalfs + col) = u32x2_t{Op::pack(v[0], v[1]), Op::pack(v[2], v[3])};
+        }
+    __syncthreads();
+
+    // ---- epilogue, part 2: LDS -> global in 16-byte pieces, 32 per pixel ----
+    const int part = threadIdx.x % 32;
+    const int mch = mslice * (kDeepMbWg * 32) + part * 8;
+    if (mch >= p.M) return;
+    if (p.pool) {
+        // 2 x 2 max-pool: tile origins and sizes are even, so every window lies inside the tile; eight windows per tile
+        constexpr int kTw2 = TW / 2;
+        const int th2 = p.TH >> 1;
+        const int q = threadIdx.x / 32;
+        const int qx = q & (kTw2 - 1), r = q / kTw2, qy = r & (th2 - 1), qn = r >> (p.th_log2 - 1);
+        const int py = (ty0 >> 1) + qy, px = (tx0 >> 1) + qx, on = n0 + qn;
+        if (on >= p.N || py >= p.Hp || px >= p.Wp) return;
+        const int op = ((qn << p.th_log2) + 2 * qy) * TW + 2 * qx;
+        const u32x4_t a = *(const u32x4_t *)(tile16 + op * kRowHalfs + part * 8);
+        const u32x4_t b = *(const u32x4_t *)(tile16 + (op + 1) * kRowHalfs + part * 8);
+        const u32x4_t c = *(const u32x4_t *)(tile16 + (op + TW) * kRowHalfs + part * 8);
+        const u32x4_t d = *(const u32x4_t *)(tile16 + (op + TW + 1) * kRowHalfs + part * 8);
+        u32x4_t v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float mx[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int sh = 16 * h;
+                mx[h] = fmaxf(fmaxf(Op::widen((uint16_t)(a[i] >> sh)), Op::widen((uint16_t)(b[i] >> sh))),
+                              fmaxf(Op::widen((uint16_t)(c[i] >> sh)), Op::widen((uint16_t)(d[i] >> sh))));
+            }
+            v[i] = Op::pack(mx[0], mx[1]);
+        }
+        const int64_t o = ((int64_t)(on * p.Hp + py) * p.Wp + px) * p.M + mch;
+        __builtin_nontemporal_store(v, (u32x4_t *)(p.y + o));
+        return;
+    }
+#pragma unroll
+    for (int op = threadIdx.x / 32; op < kDeepPx; op += kDeepThreads / 32) {
+        const int po = pixtab[op];
+        if (po < 0) continue;
+        const u32x4_t v = *(const u32x4_t *)(tile16 + op * kRowHalfs + part * 8);
+        __builtin_nontemporal_store(v, (u32x4_t *)(p.y + (int64_t)po * p.M + mch));
+    }
+}
+
+template <int DTYPE, int TW, int CS>
+int launch_deep_instance(const DeepParams &p, dim3 grid, size_t lds_bytes, hipStream_t s)
+{
+    auto kern = gdws_deep_kernel<DTYPE, TW, CS>;
+    static bool raised = false;  // one flag per kernel instance
+    if (!raised) {
+        GDWS_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDeepMaxLds));
+        raised = true;
+    }
+    kern<<<grid, kDeepThreads, lds_bytes, s>>>(p);
+    GDWS_HIP_CHECK(hipGetLastError());
+    return GDWS_OK;
+}
+
+struct DeepTile {
+    int TW, TH, TN, cs;
+    size_t lds_bytes;
+    double cost;
+};
+
+// The tile of 32 output pixels (TN images x TH rows x TW columns, TW 4 or 8) that wastes the fewest lanes.
+DeepTile choose_deep_tile(int Ho, int Wo, int C, bool pool)
+{
+    DeepTile best{0, 0, 0, 0, ~(size_t)0, 1e30};
+    const int cs = C <= 256 ? 256 : 512;
+    for (int TW : {4, 8})
+        for (int TH = pool ? 2 : 1; TH * TW <= kDeepPx; TH *= 2) {
+            const int TN = kDeepPx / (TW * TH);
+            const size_t npix = (size_t)TN * (TH + 2) * (TW + 2);
+            const size_t in_bytes = npix * (cs / 2 + 4) * 4;
+            const size_t out_bytes = (size_t)kDeepPx * (kDeepMbWg * 32 + 8) * 2 + kDeepPx * 4;
+            const size_t lds = std::max(in_bytes + (size_t)kTSlotDwords * 4, out_bytes);
+            if (lds > (size_t)kDeepMaxLds) continue;
+            const double cover = (double)((Wo + TW - 1) / TW * TW) * ((Ho + TH - 1) / TH * TH) / ((double)Wo * Ho);
+            const double halo = (double)(TH + 2) * (TW + 2) / (TH * TW);
+            const double cost = cover * (1.0 + 0.15 * (halo - 1.0)) + 1e-4 * TN;
+            if (cost < best.cost) best = DeepTile{TW, TH, TN, cs, lds, cost};
+        }
+    return best;
+}
+
+}  // namespace
+
+bool deep_shape_supported(int dtype, int layout, int K, int stride, int pad, int C, int M)
+{
+    return (dtype == GDWS_BF16 || dtype == GDWS_F16) && layout == GDWS_NHWC && K == 3 && stride == 1 && pad == 1 &&
+           C > 128 && C <= 512 && (C % 8) == 0 && M >= 256 && (M % 8) == 0;
+}
+
+// Workgroups the deep kernel would launch, or 0 if it cannot take the image.
+int64_t deep_workgroups(const FusedSchedule &sc, int N, int C, int H, int W, int M, int Ho, int Wo, bool pool)
+{
+    if (!sc.valid) return 0;
+    const int64_t x_bytes = (int64_t)N * C * H * W * 2;
+    if (x_bytes >= ((int64_t)1 << 31) || (int64_t)N * H * W >= (1 << 24)) return 0;
+    if (pool && ((Ho | Wo) & 1)) return 0;
+    const DeepTile t = choose_deep_tile(Ho, Wo, C, pool);
+    if (t.lds_bytes > (size_t)kDeepMaxLds) return 0;
+    return (int64_t)((Wo + t.TW - 1) / t.TW) * ((Ho + t.TH - 1) / t.TH) * ((N + t.TN - 1) / t.TN) *
+           ((M + kDeepMbWg * 32 - 1) / (kDeepMbWg * 32));
+}
+
+int launch_fused_deep(const FusedArgs &a, hipStream_t s)
+{
+    const FusedSchedule &sc = *a.sched;
+    if (!sc.valid || a.layout != GDWS_NHWC || a.stride != 1) return GDWS_EUNSUPPORTED;
+    if (!deep_workgroups(sc, a.N, a.C, a.H, a.W, a.M, a.Ho, a.Wo, a.pool != 0)) return GDWS_EUNSUPPORTED;
+    if (a.pool && a.ep.residual) return GDWS_EUNSUPPORTED;
+    if (sc.n_rowblocks % 4 || sc.m_blocks_pad % kDeepMbWg) return GDWS_EINVAL;  // (not a deep schedule)
+    const DeepTile t = choose_deep_tile(a.Ho, a.Wo, a.C, a.pool != 0);
+    DeepParams p;
+    p.x = (const uint16_t *)a.x; p.y = (uint16_t *)a.y;
+    p.residual = (const uint16_t *)a.ep.residual; p.bias = sc.d_bias_pad;
+    p.rec_a = (const u32x4_t *)sc.d_records;
+    p.rec_b = (const u32x2_t *)(sc.d_records + (size_t)sc.record_slots * 64 * 4);
+    p.pwfrag = (const u32x4_t *)sc.d_pwfrag;
+    p.n_groups = sc.n_rowblocks / 4; p.m_blocks_pad = sc.m_blocks_pad; p.relu = a.ep.relu;
+    p.N = a.N; p.C = a.C; p.H = a.H; p.W = a.W; p.M = a.M; p.Ho = a.Ho; p.Wo = a.Wo;
+    p.TH = t.TH; p.TN = t.TN; p.IH = t.TH + 2;
+    p.th_log2 = 0;
+    while ((1 << p.th_log2) < t.TH) ++p.th_log2;
+    p.x_bytes = (uint32_t)((int64_t)a.N * a.C * a.H * a.W * 2);
+    p.tiles_x = (a.Wo + t.TW - 1) / t.TW;
+    p.tiles_y = (a.Ho + t.TH - 1) / t.TH;
+    p.tslot_off = t.TN * (t.TH + 2) * (t.TW + 2) * (t.cs / 2 + 4);
+    p.pool = a.pool; p.Hp = a.Ho / 2; p.Wp = a.Wo / 2;
+    const int tiles_n = (a.N + t.TN - 1) / t.TN;
+    const dim3 grid((unsigned)((int64_t)p.tiles_x * p.tiles_y * tiles_n), (unsigned)(sc.m_blocks_pad / kDeepMbWg));
+#define GDWS_DEEP_CASE(DT_, TW_, CS_) \
+    if (a.dtype == DT_ && t.TW == TW_ && t.cs == CS_) return launch_deep_instance<DT_, TW_, CS_>(p, grid, t.lds_bytes, s);
+    GDWS_DEEP_CASE(GDWS_BF16, 4, 256) GDWS_DEEP_CASE(GDWS_BF16, 4, 512) GDWS_DEEP_CASE(GDWS_BF16, 8, 256)
+    GDWS_DEEP_CASE(GDWS_BF16, 8, 512) GDWS_DEEP_CASE(GDWS_F16, 4, 256) GDWS_DEEP_CASE(GDWS_F16, 4, 512)
+    GDWS_DEEP_CASE(GDWS_F16, 8, 256) GDWS_DEEP_CASE(GDWS_F16, 8, 512)
+#undef GDWS_DEEP_CASE
+    return GDWS_EUNSUPPORTED;
+}
+
+}  // namespace gdws

@@ -467,11 +467,30 @@ def test_narrow_images(case, dtype, residual):
                 residual=residual, relu=(case % 2 == 1))
 
 
+# few pixels, many channels (the deep layers of the networks): the kernel whose four waves share a 32-pixel block and
+# split the output channels.  Channel counts that are no multiples of 16 / 256, both LDS pixel sizes (C up to 256, up
+# to 512), four- and eight-pixel tile rows, 2 x 2 images (half the lanes idle), odd image sizes, a partial last slice
+# of output channels; batch sizes chosen so that the library's grid rule takes that kernel.
+DEEP = [(64, 264, 4, 4, 264), (128, 256, 2, 2, 512), (32, 512, 7, 7, 256), (40, 160, 8, 8, 512), (130, 136, 3, 4, 384),
+        (33, 200, 5, 6, 320), (70, 512, 4, 4, 512)]
+
+
+@pytest.mark.parametrize("residual", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("case", range(len(DEEP)))
+def test_deep_layers(case, dtype, residual):
+    N, C, H, W, M = DEEP[case]
+    g = _g("u14" if case % 2 == 0 else "u09", C, 4900 + case)
+    check_layer(4910 + 10 * case, N, C, H, W, M, 3, 1, 1, g, dtype, "nhwc", gd.MODE_FUSED, bias=True,
+                residual=residual, relu=(case % 2 == 1))
+
+
 # the layer with the 2 x 2 max-pool in its epilogue: one and several images per tile, odd sizes (the last row and
 # column drop out of the pool), stride 2, both stage-size classes, 64- and 128-channel workgroups, 128-pixel tiles
 POOLED = [(3, 32, 16, 16, 128, 1), (2, 16, 13, 11, 64, 1), (5, 64, 8, 8, 256, 1), (2, 24, 18, 34, 40, 2),
           (1, 128, 32, 32, 128, 1), (7, 16, 4, 4, 64, 1), (4, 16, 2, 2, 32, 1), (2, 144, 9, 40, 96, 1), (3, 16, 3, 19, 64, 1),
-          (2100, 16, 4, 4, 32, 1), (4200, 16, 2, 2, 64, 1)]   # (four-pixel tile rows)
+          (2100, 16, 4, 4, 32, 1), (4200, 16, 2, 2, 64, 1),   # (four-pixel tile rows)
+          (64, 264, 4, 4, 264, 1), (128, 256, 2, 2, 512, 1), (40, 160, 8, 8, 512, 1), (36, 384, 6, 6, 256, 1)]  # (deep layers)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
