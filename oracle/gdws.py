@@ -8,7 +8,7 @@ C x H x W order with a leading batch axis; weights are [M, C, K, K]; the K^2
 entries of one channel of one filter are vectorised row-major (u*K + v).
 
 Parity status: every function here is pinned by tests/test_oracle_*.py against
-closed forms, identities, brute force or the paper's worked example, except the
+closed forms, identities, brute force, a library routine or the paper's worked example, except the
 choice between the two readings of the error-constrained greedy's stopping rule
 (`lego(..., compare=...)`): the default follows the theorem and its proof and is
 pinned by brute force; the literal algorithm-box variant is "parity unpinned".
@@ -390,6 +390,52 @@ def gdws_forward(x, g, D, Pw, bias=None, residual=None, relu=False, stride=1, pa
     if residual is not None or relu:
         y = add_relu(y, residual, relu)
     return (y, m1 + m2) if return_macs else y
+
+
+def gdws_backward(x, g, D, Pw, dy, stride=1, pad=0, threads=1):
+    """Gradients of L through the linear map Y = PW(GDW(X)) + bias, given dy = dL/dY (what fine-tuning a GDWS
+    network needs, Section 4's fine-tuning ablation; the paper prints no formulas: these are the adjoints of the
+    two operators of Section 3.1, written out).
+
+    x [N,C,H,W], D [G,K,K], Pw [M,G], dy [N,M,H',W'].  Returns (dx [N,C,H,W], dD [G,K,K], dPw [M,G], dbias [M]):
+      T          = GDW(x)                                        (recomputed)
+      dbias[m]   = sum_{n,p} dy[n,m,p]
+      dPw[m,j]   = sum_{n,p} dy[n,m,p] T[n,j,p]
+      dT[n,j,p]  = sum_m Pw[m,j] dy[n,m,p]
+      dD[j,u,v]  = sum_{n,y,x} dT[n,j,y,x] X[n,chan_of[j], y s + u - pad, x s + v - pad]     (zero outside)
+      dx[n,c,.]  = sum_{j in channel c} sum_{u,v} D[j,u,v] dT[n,j,y,x] scattered to (y s + u - pad, x s + v - pad)
+    A ReLU or a residual add after the layer is the caller's: dy is the gradient at the layer's linear output.
+    """
+    x, D, Pw, dy = _f64(x), _f64(D), _f64(Pw), _f64(dy)
+    g = np.ascontiguousarray(g, dtype=np.int32)
+    N, C, H, Wd = x.shape
+    G, K, _ = D.shape
+    M = Pw.shape[0]
+    Ho, Wo = _osz(H, K, stride, pad), _osz(Wd, K, stride, pad)
+    assert dy.shape == (N, M, Ho, Wo) and Pw.shape == (M, G)
+    T = gdw(x, g, D, stride, pad, threads)
+    dbias = dy.sum(axis=(0, 2, 3))
+    dPw = np.zeros((M, G))
+    for m in range(M):
+        dPw[m] = (dy[:, m][:, None] * T).sum(axis=(0, 2, 3))
+    dT = np.zeros((N, G, Ho, Wo))
+    for j in range(G):
+        for m in range(M):
+            dT[:, j] += Pw[m, j] * dy[:, m]
+    xp = np.zeros((N, C, H + 2 * pad, Wd + 2 * pad))
+    xp[:, :, pad:pad + H, pad:pad + Wd] = x
+    dxp = np.zeros_like(xp)
+    ch = chan_of(g)
+    dD = np.zeros((G, K, K))
+    for j in range(G):
+        c = int(ch[j])
+        for u in range(K):
+            for v in range(K):
+                # input positions (y s + u, x s + v) of the padded image, for all output positions (y, x)
+                window = (slice(None), c, slice(u, u + (Ho - 1) * stride + 1, stride), slice(v, v + (Wo - 1) * stride + 1, stride))
+                dD[j, u, v] = (dT[:, j] * xp[window]).sum()
+                dxp[window] += D[j, u, v] * dT[:, j]
+    return dxp[:, :, pad:pad + H, pad:pad + Wd].copy(), dD, dPw, dbias
 
 
 def network_forward(layers, params, x, store=None, round_intermediate=None, threads=1, keep=False):
