@@ -35,9 +35,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the workload's default)")
     ap.add_argument("--warmup", type=int, default=-1, help="untimed steps before them (-1 = the workload's default)")
     ap.add_argument("--workload", default="config2",
-                    choices=["config2", "config2_g9", "config2_g1", "config2_dense"] + sorted(NETWORKS),
+                    choices=["config2", "config2_g9", "config2_g1", "config2_dense", "config2_backward"] + sorted(NETWORKS),
                     help="config2 (default, the headline layer), its two sub-runs, the standard convolution it "
-                         "approximates (config2_dense: conv_dense_forward on the same shape), or a network-shaped "
+                         "approximates (config2_dense: conv_dense_forward on the same shape), the layer's backward "
+                         "pass (config2_backward: gdws_backward, all four gradients), or a network-shaped "
                          "workload (VGG-16 fp16 batch 256, ResNet-18 bf16 batch 512, WRN-28-4 bf16 batch 256 at 32x32; "
                          "ResNet-50 bf16 batch 128 at 224x224)")
     ap.add_argument("--batch", type=int, default=0, help="network workloads: batch size (0 = the workload's own); "
@@ -216,6 +217,69 @@ def run_network(a):
                                "rel_l2_gpu_vs_oracle": rel_l2(yh, ref)}
     print(json.dumps(out))
 
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def run_backward(a):
+    """gdws_backward on config 2 (dx, dD, dPw, dbias): general vector-ALU kernels, priced against the fp32 vector peak."""
+    import numpy as np
+    import torch
+    import paper_2110_14871_amd as gd
+    import workloads
+    from gpu_util import empty_act, from_device, rel_l2, to_device
+
+    torch.cuda.set_device(0)
+    steps = a.steps or 200
+    warmup = a.warmup if a.warmup >= 0 else 20
+    c2 = workloads.config2(N=256)
+    N, C, H, W, M, K = c2["N"], c2["C"], c2["H"], c2["W"], c2["M"], c2["K"]
+    dtype = "bf16"
+    s, r = gd.gdws_singular_values(c2["Wt"])
+    g = gd.gdws_mego(s, r, gd.gdws_budget_gamma(c2["rho"], C, K, M), g_init=np.ones(C, np.int32), cap=9)
+    G = int(g.sum())
+    plan = gd.gdws_plan(gd.make_desc(C, M, K, 1, 1, dtype, a.layout), g, W=c2["Wt"])
+    stream = torch.cuda.Stream()
+    xd, x_exact = to_device(c2["X"], dtype, a.layout)
+    dyd, dy_exact = to_device(workloads.rng.normal(13, (N, M, H, W)), dtype, a.layout)
+    dx = empty_act(N, C, H, W, dtype, a.layout)
+    d_dw = torch.empty(G, K, K, dtype=torch.float32, device="cuda")
+    d_pw = torch.empty(M, G, dtype=torch.float32, device="cuda")
+    d_b = torch.empty(M, dtype=torch.float32, device="cuda")
+    ws = torch.empty(gd.gdws_backward_workspace_bytes(plan, N, H, W), dtype=torch.uint8, device="cuda")
+
+    def step(k):
+        gd.gdws_backward(plan, xd, dyd, N, H, W, dx=dx, d_dw=d_dw, d_pw=d_pw, d_bias=d_b, workspace=ws, stream=stream)
+
+    stepper = Stepper(gd, step, 1, stream, not a.no_graph)
+    clock_ramp(stepper, a.ramp_ms)
+    wall_ms, dev_ms = timed(stepper, steps, warmup)
+    # the intermediate and its gradient (K^2 + M products per element each), dPw (M), dD and dx (K^2 each)
+    flops = 2.0 * N * H * W * G * (3 * K * K + 2 * M)
+    tflops = flops / (dev_ms * 1e-3) / 1e12
+    out = {
+        "metric": "GDWS layer backward passes (images/sec) at batch 256", "value": N / (wall_ms * 1e-3), "unit": "images/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall_ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config2_backward: gdws_backward (dx, dD, dPw, dbias) bf16 N=256 C=128 16x16 K=3 M=128 G={G}",
+                   "layout": a.layout, "path": "general vector-ALU kernels, intermediate and its gradient in fp32 through HBM",
+                   "launch": "eager" if a.no_graph else "launch graph of 1 step"},
+        "roofline": {"bound": "alu", "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP32_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel_ms": dev_ms, "flops": flops},
+    }
+    if not a.no_cpu_baseline:
+        import oracle
+        dwq, pwq = gd.gdws_plan_factors(plan)
+        n1 = 4
+        t0 = time.perf_counter()
+        ref = oracle.gdws_backward(x_exact[:n1], g, dwq, pwq, dy_exact[:n1], 1, 1, threads=oracle_threads())
+        dt = time.perf_counter() - t0
+        # dx of an image depends on that image alone: checked on the sample
+        err = rel_l2(from_device(dx, dtype, a.layout)[:n1], ref[0])
+        out["cpu_baseline"] = {"value": n1 / dt, "unit": "images/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {n1} images, one pass of the numpy loops over filters and taps, {dt:.2f} s",
+                               "rel_l2_dx_gpu_vs_oracle": err}
+    print(json.dumps(out))
+
 
 def main():
     a = parse()
@@ -225,6 +289,8 @@ def main():
         sys.exit(2)
     if a.workload in NETWORKS:
         return run_network(a)
+    if a.workload == "config2_backward":
+        return run_backward(a)
 
     import numpy as np
     import torch

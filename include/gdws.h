@@ -213,6 +213,31 @@ int gdws_gdw_forward(const gdws_plan_t *plan, const void *x, void *t, int32_t N,
 int gdws_pw_forward(const gdws_plan_t *plan, const void *t, const void *residual, void *y, int32_t N,
                     int32_t Ho, int32_t Wo, void *stream);
 
+/* ---- backward pass (fine-tuning a GDWS network, Section 4) ------------------- */
+
+/* Gradients through the layer's linear part Y = PW(GDW(X)) + bias (the two
+ * operators of Section 3.1 Definition; the paper fine-tunes GDWS networks in
+ * its ablation but prints no formulas: these are the operators' adjoints).
+ * dy = dL/dY at the layer's linear output: a ReLU or residual add that the
+ * plan's epilogue applies in the forward pass is the caller's to undo (mask
+ * dy with y > 0 first); the desc's relu / has_residual flags are ignored here.
+ *   dx     dev, like x (the plan's dtype and layout), out, or NULL
+ *   d_dw   dev fp32 [G][K][K] out, or NULL:  dL/dD
+ *   d_pw   dev fp32 [M][G]    out, or NULL:  dL/dW_P
+ *   d_bias dev fp32 [M]       out, or NULL
+ * x dev [N,C,H,W] / [N,H,W,C], dy dev [N,M,H',W'] / [N,H',W',M] in the plan's
+ * dtype.  The factors are the plan's (as rounded to its dtype); accumulation is
+ * fp32; results are deterministic (no atomics).  workspace: device memory of
+ * gdws_backward_workspace_bytes (the intermediate and its gradient in fp32,
+ * and the per-slab partial sums of the reductions over pixels),
+ * caller-owned; GDWS_EWORKSPACE if missing or too small.  Asynchronous on
+ * `stream`, allocates nothing.  General kernels on the vector ALUs for every
+ * dtype / layout / K / stride / pad: not tuned. */
+size_t gdws_backward_workspace_bytes(const gdws_plan_t *plan, int32_t N, int32_t H, int32_t W);
+int gdws_backward(const gdws_plan_t *plan, const void *x, const void *dy, void *dx, float *d_dw, float *d_pw,
+                  float *d_bias, int32_t N, int32_t H, int32_t W, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
 /* ---- reference point: the standard convolution (eq. 1) ---------------------- */
 
 /* Bytes of device workspace conv_dense_forward needs: room for a copy of w

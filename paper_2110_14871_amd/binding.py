@@ -68,6 +68,8 @@ def lib():
             "gdws_forward_static": (ctypes.c_int, [vp, vp, vp, vp, i32, i32, i32, vp]),
             "gdws_gdw_forward": (ctypes.c_int, [vp, vp, vp, i32, i32, i32, vp]),
             "gdws_pw_forward": (ctypes.c_int, [vp, vp, vp, vp, i32, i32, i32, vp]),
+            "gdws_backward_workspace_bytes": (sz, [vp, i32, i32, i32]),
+            "gdws_backward": (ctypes.c_int, [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]),
             "conv_dense_workspace_bytes": (sz, [pdesc]),
             "conv_dense_forward": (ctypes.c_int, [pdesc, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]),
             "gdws_net_create": (ctypes.c_int, [ctypes.POINTER(NetLayer), i32, ctypes.POINTER(vp)]),
@@ -90,7 +92,7 @@ EXPORTS = ("gdws_strerror", "gdws_singular_values", "gdws_singular_values_device
            "gdws_compact_factors", "gdws_plan_sparse", "gdws_plan", "gdws_plan_destroy",
            "gdws_plan_info", "gdws_plan_factors", "gdws_intermediate_channels", "gdws_workspace_bytes", "gdws_forward",
            "gdws_forward_maxpool2", "gdws_forward_static", "gdws_gdw_forward",
-           "gdws_pw_forward", "conv_dense_workspace_bytes", "conv_dense_forward", "gdws_net_create",
+           "gdws_pw_forward", "gdws_backward_workspace_bytes", "gdws_backward", "conv_dense_workspace_bytes", "conv_dense_forward", "gdws_net_create",
            "gdws_net_destroy", "gdws_net_workspace_bytes", "gdws_network_forward", "gdws_capture_begin",
            "gdws_capture_end", "gdws_graph_launch", "gdws_graph_destroy")
 
@@ -301,6 +303,17 @@ def gdws_gdw_forward(plan, x, t, N, H, W, stream=None):
 def gdws_pw_forward(plan, t, y, N, Ho, Wo, residual=None, stream=None):
     _check(lib().gdws_pw_forward(plan.handle, _dev(t), _dev(residual), _dev(y), N, Ho, Wo, _stream(stream)),
            "gdws_pw_forward")
+
+
+def gdws_backward_workspace_bytes(plan, N, H, W):
+    return lib().gdws_backward_workspace_bytes(plan.handle, N, H, W)
+
+
+def gdws_backward(plan, x, dy, N, H, W, dx=None, d_dw=None, d_pw=None, d_bias=None, workspace=None, stream=None):
+    """Gradients through the layer's linear part; the outputs given (GPU tensors) are filled, the others skipped."""
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().gdws_backward(plan.handle, _dev(x), _dev(dy), _dev(dx), _dev(d_dw), _dev(d_pw), _dev(d_bias), N, H, W,
+                               _dev(workspace), nbytes, _stream(stream)), "gdws_backward")
 
 
 def conv_dense_workspace_bytes(desc):

@@ -549,6 +549,34 @@ int gdws_forward(const gdws_plan_t *plan, const void *x, const void *residual, v
     return run_pw(plan, workspace, residual, y, N, Ho, Wo, s);
 }
 
+size_t gdws_backward_workspace_bytes(const gdws_plan_t *plan, int32_t N, int32_t H, int32_t W)
+{
+    if (!plan) return 0;
+    int Ho, Wo;
+    if (check_image(plan->desc, N, H, W, &Ho, &Wo)) return 0;
+    return backward_workspace_bytes(N, plan->desc.M, plan->G, plan->desc.K, Ho, Wo);
+}
+
+int gdws_backward(const gdws_plan_t *plan, const void *x, const void *dy, void *dx, float *d_dw, float *d_pw,
+                  float *d_bias, int32_t N, int32_t H, int32_t W, void *workspace, size_t workspace_bytes,
+                  void *stream)
+{
+    if (!plan || !x || !dy) return GDWS_ENULL;
+    int Ho, Wo;
+    const int rc = check_image(plan->desc, N, H, W, &Ho, &Wo);
+    if (rc) return rc;
+    if (!workspace || workspace_bytes < backward_workspace_bytes(N, plan->desc.M, plan->G, plan->desc.K, Ho, Wo))
+        return GDWS_EWORKSPACE;
+    const gdws_layer_desc_t &d = plan->desc;
+    BackwardArgs a;
+    a.x = x; a.dy = dy; a.dx = dx; a.g_dw = d_dw; a.g_pw = d_pw; a.g_bias = d_bias;
+    a.dw = plan->d_dw; a.pw = plan->d_pw; a.offsets = plan->d_offsets; a.chan_of = plan->d_chan_of;
+    a.workspace = workspace; a.dtype = d.dtype; a.layout = d.layout;
+    a.N = N; a.C = d.C; a.H = H; a.W = W; a.M = d.M; a.G = plan->G; a.K = d.K; a.stride = d.stride; a.pad = d.pad;
+    a.Ho = Ho; a.Wo = Wo;
+    return launch_backward(a, (hipStream_t)stream);
+}
+
 int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32_t N, int32_t H, int32_t W,
                           void *stream)
 {

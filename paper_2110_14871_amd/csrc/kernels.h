@@ -100,6 +100,20 @@ bool conv_mfma_supported(int dtype, int layout, int K, int stride, int pad, int 
 size_t conv_mfma_workspace_bytes(int C, int M);
 int launch_conv_mfma(const DenseArgs &a, void *workspace, hipStream_t s);
 
+// Backward pass through the layer's linear part (kernels_backward.hip).  Gradient outputs that are nullptr are skipped.
+struct BackwardArgs {
+    const void *x, *dy;        // activations in the layer's storage type and layout
+    void *dx;                  // like x, or nullptr
+    float *g_dw, *g_pw, *g_bias;  // fp32 [G][K][K], [M][G], [M], or nullptr
+    const float *dw, *pw;      // the plan's factors (fp32 copies of the rounded values)
+    const int32_t *offsets, *chan_of;
+    void *workspace;           // backward_workspace_bytes
+    int dtype, layout;
+    int N, C, H, W, M, G, K, stride, pad, Ho, Wo;
+};
+size_t backward_workspace_bytes(int N, int M, int G, int K, int Ho, int Wo);
+int launch_backward(const BackwardArgs &a, hipStream_t s);
+
 // Singular values (descending), numerical rank and, optionally, right singular vectors of the C slices W_c (M x K^2)
 // of a weight [M][C][K][K] in device memory: one wave per slice, Jacobi on the Gram matrix in fp64.  K <= 7.
 int launch_svd_device(const float *w, int M, int C, int K, double *sigma, int32_t *rank, double *v, hipStream_t s);

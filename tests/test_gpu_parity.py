@@ -734,3 +734,71 @@ def test_singular_values_device(case):
             gap = min([abs(S[c, i] - S[c, j]) for j in range(R) if j != i] + [S[c, i]])
             if gap > 1e-6 * s1:
                 assert np.allclose(Vc[i], Vt[c, i], atol=1e-7 * s1 / gap)
+
+
+# ------------------------------------------------------------------------------------------
+# backward pass through the layer's linear part (fine-tuning)
+# ------------------------------------------------------------------------------------------
+
+BACKWARD = [
+    # N, C, H, W, M, K, stride, pad, g-rule
+    (2, 16, 12, 12, 24, 3, 1, 1, "u13"),
+    (3, 10, 9, 11, 7, 3, 2, 1, "u09"),       # stride 2, odd sizes, channels without filters
+    (1, 6, 9, 9, 12, 5, 1, 2, "u13"),        # K = 5
+    (2, 8, 8, 8, 20, 3, 2, 0, "u13"),        # no padding: the last row and column of x get no gradient
+    (2, 12, 5, 5, 9, 1, 1, 0, "u13"),        # K = 1
+    (4, 40, 16, 16, 48, 3, 1, 1, "u14"),     # several tiles of every kernel
+]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("case", range(len(BACKWARD)))
+def test_backward(case, dtype, layout):
+    N, C, H, W, M, K, stride, pad, rule = BACKWARD[case]
+    seed = 5200 + 10 * case
+    g = _g(rule, C, seed)
+    G = int(g.sum())
+    Ho, Wo = _osz(H, K, stride, pad), _osz(W, K, stride, pad)
+    x = rng.normal(seed, (N, C, H, W))
+    dw = rng.normal(seed + 1, (G, K, K), std=0.3)
+    pw = rng.normal(seed + 2, (M, G), std=0.3)
+    dy = rng.normal(seed + 3, (N, M, Ho, Wo))
+    desc = gd.make_desc(C, M, K, stride, pad, dtype, layout)
+    plan = gd.gdws_plan(desc, g, dw=dw, pw=pw)
+    dwq, pwq = gd.gdws_plan_factors(plan)
+    xd, x_exact = to_device(x, dtype, layout)
+    dyd, dy_exact = to_device(dy, dtype, layout)
+    dx = empty_act(N, C, H, W, dtype, layout, fill=float("nan"))
+    d_dw = torch.full((G, K, K), float("nan"), dtype=torch.float32, device="cuda")
+    d_pw = torch.full((M, G), float("nan"), dtype=torch.float32, device="cuda")
+    d_b = torch.full((M,), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = gd.gdws_backward_workspace_bytes(plan, N, H, W)
+    assert nbytes >= 2 * N * G * Ho * Wo * 4
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(gd.GdwsError):
+        gd.gdws_backward(plan, xd, dyd, N, H, W, dx=dx, workspace=ws[:nbytes - 4])
+    gd.gdws_backward(plan, xd, dyd, N, H, W, dx=dx, d_dw=d_dw, d_pw=d_pw, d_bias=d_b, workspace=ws)
+    torch.cuda.synchronize()
+    rdx, rdD, rdP, rdb = oracle.gdws_backward(x_exact, g, dwq, pwq, dy_exact, stride, pad)
+    # weight gradients: fp32 sums of exact products of the (rounded) inputs; dx is rounded to the storage type
+    for got, ref in ((d_dw, rdD), (d_pw, rdP), (d_b, rdb)):
+        got = got.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        assert rel_l2(got, ref) <= 1e-5
+    dxh = from_device(dx, dtype, layout)
+    assert np.isfinite(dxh).all()
+    assert rel_l2(dxh, rdx) <= TOL[dtype]
+    # element by element: fp32 accumulation of the sums' absolute terms, plus the storage rounding of dx
+    a_dx, a_dD, a_dP, a_db = oracle.gdws_backward(np.abs(x_exact), g, np.abs(dwq), np.abs(pwq), np.abs(dy_exact), stride, pad)
+    terms = N * Ho * Wo + G * K * K + M
+    ulp = {"f32": 2.0 ** -24, "f16": 2.0 ** -11, "bf16": 2.0 ** -8}[dtype]
+    assert (np.abs(d_dw.cpu().numpy() - rdD) <= terms * 2.0 ** -23 * a_dD + 1e-30).all()
+    assert (np.abs(d_pw.cpu().numpy() - rdP) <= terms * 2.0 ** -23 * a_dP + 1e-30).all()
+    assert (np.abs(dxh - rdx) <= terms * 2.0 ** -23 * a_dx + ulp * 1.01 * np.abs(rdx) + 1e-30).all()
+    # a second call that asks for dx only leaves the other buffers alone
+    d_pw.fill_(7.0)
+    gd.gdws_backward(plan, xd, dyd, N, H, W, dx=dx, workspace=ws)
+    torch.cuda.synchronize()
+    assert (d_pw == 7.0).all() and (from_device(dx, dtype, layout) == dxh).all()
