@@ -155,8 +155,13 @@ int gdws_plan_factors(const gdws_plan_t *plan, float *dw_out, float *pw_out);
 
 /* ---- forward (Section 3.1 Definition) -------------------------------------- */
 
-/* Bytes of device workspace gdws_forward needs for this shape and mode (0 for
- * the fused path; the G-channel intermediate for the unfused path). */
+/* Bytes of device workspace gdws_forward uses for this shape and mode: the
+ * G-channel intermediate for the unfused path (required).  For the fused path
+ * 0, except for small launches of deep layers (a batch of one or two images,
+ * more than 128 input channels): there the row blocks are split over
+ * workgroups and the fp32 partial sums pass through this much workspace.  That
+ * workspace is optional: without it (NULL, or fewer bytes) the same call runs
+ * unsplit, slower, with the same results up to the order of the fp32 sums. */
 size_t gdws_workspace_bytes(const gdws_plan_t *plan, int32_t N, int32_t H, int32_t W, int mode);
 
 /* y = epilogue(PW(GDW(x))).  x dev [N,C,H,W] / [N,H,W,C]; y dev [N,M,H',W'] /

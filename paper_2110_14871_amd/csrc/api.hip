@@ -50,7 +50,7 @@ struct gdws_plan_s {
         (void)hipFree(fused.d_pwfrag); (void)hipFree(fused.d_bias_pad);
         (void)hipFree(gdwm.d_stage_tab); (void)hipFree(gdwm.d_records); (void)hipFree(gdwm.d_bias_pad);
         (void)hipFree(deep.d_stage_tab); (void)hipFree(deep.d_records); (void)hipFree(deep.d_pwfrag);
-        (void)hipFree(deep.d_bias_pad);
+        (void)hipFree(deep.d_bias_pad); (void)hipFree(deep.d_group_chan);
         (void)hipFree(pwm.d_frag); (void)hipFree(pwm.d_bias_pad); (void)hipFree(gdl.d_chunks);
         (void)hipFree(gdm.d_frag); (void)hipFree(gdm.d_bias_pad);
     }
@@ -233,8 +233,15 @@ constexpr int64_t kDeepMinWorkgroups = 64;
 constexpr int64_t kDeepMaxPixels = 6400;   // output pixels of the batch above which the general kernel's tiles fill the chip
                                            // (measured: 4,096 and 6,272 pixels gain 10 to 30 %, 8,192 and 16,384 are even)
 
+// Workspace with which the fused path splits a small launch of a deep layer (0: no such split for this call).
+size_t fused_split_bytes(const gdws_plan_t *p, int N, int H, int W, int Ho, int Wo, bool pool)
+{
+    if (!p->deep.valid || (int64_t)N * Ho * Wo > kDeepMaxPixels) return 0;
+    return deep_split_workspace_bytes(p->deep, N, p->desc.C, H, W, p->desc.M, Ho, Wo, pool);
+}
+
 int run_fused(const gdws_plan_t *p, const void *x, const void *residual, void *y, int N, int H, int W, int Ho, int Wo,
-              hipStream_t s, int pool = 0)
+              hipStream_t s, int pool = 0, void *ws = nullptr, size_t ws_bytes = 0)
 {
     FusedArgs a;
     a.pool = pool;
@@ -242,13 +249,18 @@ int run_fused(const gdws_plan_t *p, const void *x, const void *residual, void *y
     a.dtype = p->desc.dtype; a.layout = p->desc.layout; a.stride = p->desc.stride;
     a.N = N; a.C = p->desc.C; a.H = H; a.W = W; a.M = p->desc.M; a.Ho = Ho; a.Wo = Wo;
     // Few pixels and many channels: the kernel whose waves split the output channels of one 32-pixel block, when its
-    // grid gives the chip enough workgroups.
-    if (deep_workgroups(p->deep, N, a.C, H, W, a.M, Ho, Wo, pool != 0) >= kDeepMinWorkgroups &&
-        (int64_t)N * Ho * Wo <= kDeepMaxPixels && !(pool && a.ep.residual)) {
-        FusedArgs d = a;
-        d.sched = &p->deep;
-        const int rc = launch_fused_deep(d, s);
-        if (rc != GDWS_EUNSUPPORTED) return rc;
+    // grid gives the chip enough workgroups -- or, for the smallest launches, when the caller's workspace lets it
+    // split the row blocks over workgroups as well.
+    const int64_t dwg = deep_workgroups(p->deep, N, a.C, H, W, a.M, Ho, Wo, pool != 0);
+    if (dwg > 0 && (int64_t)N * Ho * Wo <= kDeepMaxPixels && !(pool && a.ep.residual)) {
+        const size_t split = fused_split_bytes(p, N, H, W, Ho, Wo, pool != 0);
+        const bool can_split = split > 0 && ws && ws_bytes >= split;
+        if (dwg >= kDeepMinWorkgroups || can_split) {
+            FusedArgs d = a;
+            d.sched = &p->deep;
+            const int rc = launch_fused_deep(d, can_split ? ws : nullptr, can_split ? ws_bytes : 0, s);
+            if (rc != GDWS_EUNSUPPORTED) return rc;
+        }
     }
     return launch_fused(a, s);
 }
@@ -435,6 +447,7 @@ int plan_impl(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, c
             rc = upload(&p->deep.d_records, p->deep.records);
             if (!rc) rc = upload(&p->deep.d_pwfrag, p->deep.pwfrag);
             if (!rc) rc = upload(&p->deep.d_bias_pad, p->deep.bias_pad);
+            if (!rc) rc = upload(&p->deep.d_group_chan, p->deep.group_chan);
         }
     }
     p->Gt = G;
@@ -521,8 +534,9 @@ size_t gdws_workspace_bytes(const gdws_plan_t *plan, int32_t N, int32_t H, int32
     if (!plan) return 0;
     int Ho, Wo;
     if (check_image(plan->desc, N, H, W, &Ho, &Wo)) return 0;
+    if (mode != GDWS_MODE_UNFUSED && fused_supported(plan, N, H, W))  // (with or without a pooled epilogue)
+        return std::max(fused_split_bytes(plan, N, H, W, Ho, Wo, false), fused_split_bytes(plan, N, H, W, Ho, Wo, true));
     if (mode == GDWS_MODE_FUSED) return 0;
-    if (mode == GDWS_MODE_AUTO && fused_supported(plan, N, H, W)) return 0;
     return intermediate_bytes(plan, N, Ho, Wo);
 }
 
@@ -538,7 +552,7 @@ int gdws_forward(const gdws_plan_t *plan, const void *x, const void *residual, v
     hipStream_t s = (hipStream_t)stream;
     const bool fused_ok = fused_supported(plan, N, H, W);
     if (mode != GDWS_MODE_UNFUSED && fused_ok) {
-        rc = run_fused(plan, x, residual, y, N, H, W, Ho, Wo, s);
+        rc = run_fused(plan, x, residual, y, N, H, W, Ho, Wo, s, 0, workspace, workspace_bytes);
         if (rc != GDWS_EUNSUPPORTED) return rc;
     }
     // asked for the fused path on a shape the matrix-core kernel does not take: the vector-ALU fused kernel
@@ -577,8 +591,12 @@ int gdws_backward(const gdws_plan_t *plan, const void *x, const void *dy, void *
     return launch_backward(a, (hipStream_t)stream);
 }
 
-int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32_t N, int32_t H, int32_t W,
-                          void *stream)
+}  // extern "C"
+
+namespace {
+
+int forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32_t N, int32_t H, int32_t W, void *ws,
+                     size_t ws_bytes, void *stream)
 {
     if (!plan || !x || !y) return GDWS_ENULL;
     int Ho, Wo;
@@ -590,7 +608,17 @@ int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32
     // workgroups store pooled rows while others still read x: the two tensors must not share memory
     if (ranges_overlap(x, (size_t)N * plan->desc.C * H * W * 2, y, (size_t)N * plan->desc.M * (Ho / 2) * (Wo / 2) * 2))
         return GDWS_EINVAL;
-    return run_fused(plan, x, nullptr, y, N, H, W, Ho, Wo, (hipStream_t)stream, 1);
+    return run_fused(plan, x, nullptr, y, N, H, W, Ho, Wo, (hipStream_t)stream, 1, ws, ws_bytes);
+}
+
+}  // namespace
+
+extern "C" {
+
+int gdws_forward_maxpool2(const gdws_plan_t *plan, const void *x, void *y, int32_t N, int32_t H, int32_t W,
+                          void *stream)
+{
+    return forward_maxpool2(plan, x, y, N, H, W, nullptr, 0, stream);
 }
 
 int gdws_gdw_forward(const gdws_plan_t *plan, const void *x, void *t, int32_t N, int32_t H, int32_t W, void *stream)
@@ -770,7 +798,7 @@ int run_network(const gdws_net_t *net, const NetLayout &lay, const void *x, void
         if (n.l.kind == GDWS_LAYER_GDWS && pooled_by_next(net, i)) {
             // the 2 x 2 max-pool that is this layer's only reader runs in its epilogue when the kernel can
             void *pout = sh[i + 1].offset == SIZE_MAX ? y : ws + sh[i + 1].offset;
-            rc = gdws_forward_maxpool2(n.l.plan, in, pout, N, ih, iw, stream);
+            rc = forward_maxpool2(n.l.plan, in, pout, N, ih, iw, scratch, scratch_bytes, stream);
             if (rc == GDWS_OK) { ++i; continue; }
             if (rc != GDWS_EUNSUPPORTED && rc != GDWS_EINVAL) return rc;
             rc = gdws_forward(n.l.plan, in, res, outp, N, ih, iw, scratch, scratch_bytes, GDWS_MODE_AUTO, stream);

@@ -60,11 +60,14 @@ struct FusedSchedule {
     std::vector<uint32_t> records;
     std::vector<uint16_t> pwfrag;    // per row block (+1 of zeros), K-step, 32-wide block of M, lane: 8 weights
     std::vector<float> bias_pad;     // [m_blocks_pad * 32]: the bias, zero beyond M (all zero without a bias)
+    std::vector<uint32_t> group_chan;  // deep schedules: per group of four row blocks, first input channel its windows
+                                       // reach | (last + 1) << 16
     // device copies
     int32_t *d_stage_tab = nullptr;
     uint32_t *d_records = nullptr;
     uint16_t *d_pwfrag = nullptr;
     float *d_bias_pad = nullptr;
+    uint32_t *d_group_chan = nullptr;
 };
 
 // Builds the host tables from the (already rounded) factors.  dw [G][9], pw [M][G], bias [M] or nullptr.
@@ -96,6 +99,8 @@ int launch_fused(const FusedArgs &a, hipStream_t s);
 // The deep-layer kernel: few pixels, many channels (see kernels_fused_deep.hip).  a.sched is a deep schedule.
 bool deep_shape_supported(int dtype, int layout, int K, int stride, int pad, int C, int M);
 int64_t deep_workgroups(const FusedSchedule &sc, int N, int C, int H, int W, int M, int Ho, int Wo, bool pool);
-int launch_fused_deep(const FusedArgs &a, hipStream_t s);
+// Bytes of workspace with which a launch this small is split over runs of row blocks (0: it is not split).
+size_t deep_split_workspace_bytes(const FusedSchedule &sc, int N, int C, int H, int W, int M, int Ho, int Wo, bool pool);
+int launch_fused_deep(const FusedArgs &a, void *workspace, size_t workspace_bytes, hipStream_t s);
 
 }  // namespace gdws

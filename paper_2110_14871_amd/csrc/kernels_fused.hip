@@ -197,9 +197,23 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
     while (deep_stage && !rbs.empty() && rbs.size() % 4) {  // empty row blocks: no rows, no weights
         RowBlock rb{};
         for (int r = 0; r < kRowBlock; ++r) rb.rows[r] = -1;
+        // (their operands are read all the same and multiplied by zero: they take the last window, which every
+        // workgroup that runs them has loaded -- stale LDS contents could be infinities or NaNs)
+        rb.cb0 = rbs.back().cb0;
+        rb.last_chunk = rbs.back().last_chunk;
         rbs.push_back(rb);
     }
     s.n_rowblocks = (int)rbs.size();
+    if (deep_stage) {
+        // per group of four row blocks, the input channels its windows reach (padding row blocks have no rows)
+        for (size_t k = 0; k < rbs.size(); k += 4) {
+            int lo = 1 << 15, hi = 0;
+            for (size_t r = k; r < k + 4; ++r)
+                if (rbs[r].rows[0] >= 0) { lo = std::min(lo, rbs[r].cb0); hi = std::max(hi, rbs[r].cb0 + kWindow); }
+            if (hi == 0) lo = 0;
+            s.group_chan.push_back((uint32_t)lo | ((uint32_t)hi << 16));
+        }
+    }
     // all-zero records behind the last row block: the general kernel reads two row blocks ahead, the deep-layer
     // kernel two groups of four
     const size_t slots = rbs.size() + (deep_stage ? 8 : 2);

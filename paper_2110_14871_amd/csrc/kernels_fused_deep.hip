@@ -17,6 +17,12 @@
 // into LDS by the four waves before the first row block: one stage, no loader waves.  Records, pointwise
 // fragments and bias are the general kernel's (build_fused_schedule with its deep_stage argument: one stage, the
 // row blocks padded to a multiple of four, the output channels to a multiple of 256).
+//
+// Small launches (a batch of one or two images: a handful of pixel blocks) additionally split the groups of row blocks
+// over workgroups (SPLIT): workgroup z takes a run of groups, loads only the input channels those draw on, and writes
+// its fp32 partial sums to a workspace; a second kernel adds the partial sums in a fixed order, then bias, residual,
+// ReLU, rounding (and the 2 x 2 max-pool).  The chain of row blocks that one workgroup walks through is what such a
+// launch waits for; cut into S runs it is S times shorter.
 #include <algorithm>
 
 #include "fused_kernel.h"
@@ -50,10 +56,15 @@ struct DeepParams {
     int tiles_x, tiles_y;
     int tslot_off;  // dword offset in LDS of the intermediate's slots (behind the input tile)
     int pool, Hp, Wp;
+    // SPLIT: groups per workgroup, per-group channel ranges (lo | hi << 16), the partial sums [slice][pixel][channel]
+    int groups_per_slice;
+    const uint32_t *group_chan;
+    float *part;
+    int64_t part_slice;  // floats per slice: pixels of y x padded channels
 };
 
 // CS: channels the LDS tile holds per pixel (256 or 512).
-template <int DTYPE, int TW, int CS>
+template <int DTYPE, int TW, int CS, bool SPLIT>
 __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams params)
 {
     using Op = half_ops<DTYPE>;
@@ -72,11 +83,16 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
     const int mslice = blockIdx.y;                                // 256 output channels
     const int mb0 = mslice * kDeepMbWg + wave * kDeepMbWave;      // the wave's first 32-wide block of them
 
+    // the workgroup's groups of row blocks: all of them, or its run of them
+    const int g_begin = SPLIT ? (int)blockIdx.z * p.groups_per_slice : 0;
+    const int g_end = SPLIT ? min(g_begin + p.groups_per_slice, p.n_groups) : p.n_groups;
+
     // ---- records and pointwise fragments of the first group: requested before anything else ----
-    u32x4_t ra = p.rec_a[wave * 64 + lane], na = p.rec_a[(4 + wave) * 64 + lane];
-    u32x2_t rb = p.rec_b[wave * 64 + lane], nb = p.rec_b[(4 + wave) * 64 + lane];
+    const int r0 = g_begin * 4 + wave;
+    u32x4_t ra = p.rec_a[r0 * 64 + lane], na = p.rec_a[(r0 + 4) * 64 + lane];
+    u32x2_t rb = p.rec_b[r0 * 64 + lane], nb = p.rec_b[(r0 + 4) * 64 + lane];
     const int kstep_stride = p.m_blocks_pad * 64;          // 16-byte units per K-step of a row block
-    const u32x4_t *fp = p.pwfrag + (int64_t)mb0 * 64 + lane;  // (row block 0, K-step 0, the wave's blocks)
+    const u32x4_t *fp = p.pwfrag + (int64_t)g_begin * 8 * kstep_stride + (int64_t)mb0 * 64 + lane;  // (first row block, K-step 0, the wave's blocks)
     u32x4_t pwf[4][2][kDeepMbWave];
 #pragma unroll
     for (int s = 0; s < 4; ++s)
@@ -86,11 +102,36 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
             for (int mb = 0; mb < kDeepMbWave; ++mb) pwf[s][s2][mb] = fp[(s * 2 + s2) * kstep_stride + mb * 64];
 
     // ---- the input tile: 16-byte pieces, consecutive threads along a pixel's channels ----
-    {
+    constexpr uint32_t kOutside = 0x80000000u;  // beyond the descriptor's bound: the load returns zeros
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, 0x00020000);
+    if constexpr (SPLIT) {
+        // only the channels the workgroup's row blocks draw on (the rest of the tile is never read): a few pieces per
+        // pixel, dealt out over all threads so that they are in flight together
+        const int lo = (int)(p.group_chan[g_begin] & 0xffffu), hi = (int)(p.group_chan[g_end - 1] >> 16);
+        const int q_lo = lo / 8, nq = (hi + 7) / 8 - q_lo;
+        const int total = p.TN * p.IH * IW * nq;
+        constexpr int kBatch = 4;
+        for (int i0 = threadIdx.x; i0 < total; i0 += kDeepThreads * kBatch) {
+            u32x4_t v[kBatch];
+            int dst[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                const int i = i0 + kDeepThreads * k;
+                const int pix = i / nq, q = q_lo + i - pix * nq;
+                const int ix = pix % IW, r = pix / IW, iy = r % p.IH, tn = r / p.IH;
+                const int n = n0 + tn, gy = ty0 - 1 + iy, gx = tx0 - 1 + ix;
+                const bool in = i < total && q * 8 < p.C && n < p.N && (unsigned)gy < (unsigned)p.H && (unsigned)gx < (unsigned)p.W;
+                const uint32_t pixel = __umul24(__umul24(n, p.H) + gy, p.W) + gx;
+                v[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, in ? __umul24(pixel, (uint32_t)p.C * 2u) + q * 16 : kOutside, 0, 0);
+                dst[k] = i < total ? pix * PSW + q * 4 : -1;
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k)
+                if (dst[k] >= 0) *(u32x4_t *)(lds + dst[k]) = v[k];
+        }
+    } else {
         const int npix = p.TN * p.IH * IW;
         const int total = npix * QP;
-        constexpr uint32_t kOutside = 0x80000000u;  // beyond the descriptor's bound: the load returns zeros
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, 0x00020000);
         constexpr int kStepPix = kDeepThreads / QP;  // pixels from one of a thread's pieces to its next (4 or 8)
         constexpr int kStepX = kStepPix % IW, kStepY = kStepPix / IW;
         static_assert(kStepY <= 1, "the walk over the tile's pixels advances by less than two rows per step");
@@ -143,7 +184,8 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
         const float *bp = p.bias + (mb0 + mb) * 32;  // padded with zeros to whole blocks
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4_t bv = *(const f32x4_t *)(bp + 8 * q4 + 4 * lhi);
+            f32x4_t bv = *(const f32x4_t *)(bp + 8 * q4 + 4 * lhi);
+            if (SPLIT) bv = f32x4_t{0.f, 0.f, 0.f, 0.f};  // (the second kernel adds the bias)
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[mb][4 * q4 + i] = bv[i];
         }
@@ -164,7 +206,7 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
     };
     read_operands((uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]));
 
-    for (int gi = 0; gi < p.n_groups; ++gi) {
+    for (int gi = g_begin; gi < g_end; ++gi) {
         // ---- depthwise stage of row block 4 gi + wave ----
         const uint32_t sel = rb[0] >> 16;
         const uint32_t hm = (sel & 8) ? 0xFFFF0000u : 0x0000FFFFu;
@@ -233,6 +275,21 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
                     pwf[s][s2][mb] = fp[(s * 2 + s2) * kstep_stride + mb * 64];
                 }
             }
+    }
+    if constexpr (SPLIT) {
+        // ---- the partial sums leave as they are: 16 bytes (four consecutive channels) per lane and store ----
+        const int row = l32 / TW;
+        const int ox = tx0 + (l32 & (TW - 1)), oy = ty0 + (row & (p.TH - 1)), on = n0 + (row >> p.th_log2);
+        if (on >= p.N || oy >= p.Ho || ox >= p.Wo) return;
+        const int64_t pix = ((int64_t)on * p.Ho + oy) * p.Wo + ox;
+        float *dst = p.part + (int64_t)blockIdx.z * p.part_slice + pix * (p.m_blocks_pad * 32);
+#pragma unroll
+        for (int mb = 0; mb < kDeepMbWave; ++mb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *(f32x4_t *)(dst + (mb0 + mb) * 32 + 8 * q4 + 4 * lhi) =
+                    f32x4_t{acc[mb][4 * q4], acc[mb][4 * q4 + 1], acc[mb][4 * q4 + 2], acc[mb][4 * q4 + 3]};
+        return;
     }
     __syncthreads();  // every wave is done with the input tile and the slots: the output tile may overwrite them
 
@@ -311,10 +368,83 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
     }
 }
 
-template <int DTYPE, int TW, int CS>
+// Second kernel of a split launch: y (or its 2 x 2 max-pool) from the partial sums, 8 channels per thread.
+struct DeepFinishParams {
+    const float *part;
+    int64_t part_slice;
+    int slices, mpad;
+    const float *bias;  // padded to mpad
+    const uint16_t *residual;
+    uint16_t *y;
+    int relu, pool;
+    int N, M, Ho, Wo, Hp, Wp;
+};
+
+template <int DTYPE>
+__global__ __launch_bounds__(256) void gdws_deep_finish_kernel(DeepFinishParams p)
+{
+    using Op = half_ops<DTYPE>;
+    const int parts = p.M / 8;
+    // one thread per pixel of the layer's output and group of 8 channels; with the pooled epilogue the four pixels of a
+    // window are four neighbouring lanes (the two lowest bits of the thread index), which then take their maximum
+    const int64_t outs = (int64_t)p.N * (p.pool ? p.Hp * p.Wp * 4 : p.Ho * p.Wo);
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = i < outs * parts;
+    const int sub = p.pool ? (int)(i & 3) : 0;
+    const int64_t iq = p.pool ? i >> 2 : i;
+    const int part = (int)(iq % parts), mch = part * 8;
+    const int64_t o = iq / parts;
+    int64_t pix = o;
+    if (p.pool) {
+        const int px = (int)(o % p.Wp), py = (int)((o / p.Wp) % p.Hp);
+        const int64_t n = o / ((int64_t)p.Wp * p.Hp);
+        pix = (n * p.Ho + 2 * py + (sub >> 1)) * p.Wo + 2 * px + (sub & 1);
+    }
+    // partial sums in slice order, bias, residual, ReLU, rounding
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = 0.f;
+    if (live) {
+        for (int z = 0; z < p.slices; ++z) {
+            const float *src = p.part + z * p.part_slice + pix * p.mpad + mch;
+            const f32x4_t a = *(const f32x4_t *)src, b = *(const f32x4_t *)(src + 4);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { v[k] += a[k]; v[4 + k] += b[k]; }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] += p.bias[mch + k];
+        if (p.residual) {
+            const u32x4_t r = *(const u32x4_t *)(p.residual + pix * p.M + mch);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] += Op::widen((uint16_t)(r[k / 2] >> (16 * (k & 1))));
+        }
+        if (p.relu) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = relu_bits(v[k]);
+        }
+    }
+    u32x4_t out = u32x4_t{Op::pack(v[0], v[1]), Op::pack(v[2], v[3]), Op::pack(v[4], v[5]), Op::pack(v[6], v[7])};
+    if (p.pool) {
+        // the maximum of the rounded values of the window, as the separate pooling pass takes it
+#pragma unroll
+        for (int step = 1; step <= 2; step <<= 1) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t other = (uint32_t)__shfl_xor((int)out[k], step);
+                const float a0 = Op::widen((uint16_t)out[k]), a1 = Op::widen((uint16_t)(out[k] >> 16));
+                const float b0 = Op::widen((uint16_t)other), b1 = Op::widen((uint16_t)(other >> 16));
+                out[k] = Op::pack(fmaxf(a0, b0), fmaxf(a1, b1));
+            }
+        }
+        if (sub) return;
+    }
+    if (live) *(u32x4_t *)(p.y + o * p.M + mch) = out;
+}
+
+template <int DTYPE, int TW, int CS, bool SPLIT>
 int launch_deep_instance(const DeepParams &p, dim3 grid, size_t lds_bytes, hipStream_t s)
 {
-    auto kern = gdws_deep_kernel<DTYPE, TW, CS>;
+    auto kern = gdws_deep_kernel<DTYPE, TW, CS, SPLIT>;
     static bool raised = false;  // one flag per kernel instance
     if (!raised) {
         GDWS_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kDeepMaxLds));
@@ -324,6 +454,9 @@ int launch_deep_instance(const DeepParams &p, dim3 grid, size_t lds_bytes, hipSt
     GDWS_HIP_CHECK(hipGetLastError());
     return GDWS_OK;
 }
+
+constexpr int64_t kDeepSplitBelow = 64;    // workgroups below which a launch is split over runs of row-block groups
+constexpr int64_t kDeepSplitTarget = 128;  // ... into about this many workgroups
 
 struct DeepTile {
     int TW, TH, TN, cs;
@@ -373,11 +506,30 @@ int64_t deep_workgroups(const FusedSchedule &sc, int N, int C, int H, int W, int
            ((M + kDeepMbWg * 32 - 1) / (kDeepMbWg * 32));
 }
 
-int launch_fused_deep(const FusedArgs &a, hipStream_t s)
+// Split of a small launch over runs of row-block groups: the number of runs, 1 if the launch is not split.
+static int deep_slices(const FusedSchedule &sc, int64_t wgs)
+{
+    const int n_groups = sc.n_rowblocks / 4;
+    if (wgs >= kDeepSplitBelow || n_groups < 2 || sc.group_chan.empty()) return 1;
+    const int want = (int)std::min<int64_t>(n_groups, (kDeepSplitTarget + wgs - 1) / wgs);
+    const int per = (n_groups + want - 1) / want;
+    return (n_groups + per - 1) / per;
+}
+
+size_t deep_split_workspace_bytes(const FusedSchedule &sc, int N, int C, int H, int W, int M, int Ho, int Wo, bool pool)
+{
+    const int64_t wgs = deep_workgroups(sc, N, C, H, W, M, Ho, Wo, pool);
+    if (!wgs) return 0;
+    const int S = deep_slices(sc, wgs);
+    return S > 1 ? (size_t)S * N * Ho * Wo * sc.m_blocks_pad * 32 * sizeof(float) : 0;
+}
+
+int launch_fused_deep(const FusedArgs &a, void *workspace, size_t workspace_bytes, hipStream_t s)
 {
     const FusedSchedule &sc = *a.sched;
     if (!sc.valid || a.layout != GDWS_NHWC || a.stride != 1) return GDWS_EUNSUPPORTED;
-    if (!deep_workgroups(sc, a.N, a.C, a.H, a.W, a.M, a.Ho, a.Wo, a.pool != 0)) return GDWS_EUNSUPPORTED;
+    const int64_t wgs = deep_workgroups(sc, a.N, a.C, a.H, a.W, a.M, a.Ho, a.Wo, a.pool != 0);
+    if (!wgs) return GDWS_EUNSUPPORTED;
     if (a.pool && a.ep.residual) return GDWS_EUNSUPPORTED;
     if (sc.n_rowblocks % 4 || sc.m_blocks_pad % kDeepMbWg) return GDWS_EINVAL;  // (not a deep schedule)
     const DeepTile t = choose_deep_tile(a.Ho, a.Wo, a.C, a.pool != 0);
@@ -397,15 +549,40 @@ int launch_fused_deep(const FusedArgs &a, hipStream_t s)
     p.tiles_y = (a.Ho + t.TH - 1) / t.TH;
     p.tslot_off = t.TN * (t.TH + 2) * (t.TW + 2) * (t.cs / 2 + 4);
     p.pool = a.pool; p.Hp = a.Ho / 2; p.Wp = a.Wo / 2;
+    p.groups_per_slice = p.n_groups; p.group_chan = sc.d_group_chan; p.part = nullptr; p.part_slice = 0;
     const int tiles_n = (a.N + t.TN - 1) / t.TN;
-    const dim3 grid((unsigned)((int64_t)p.tiles_x * p.tiles_y * tiles_n), (unsigned)(sc.m_blocks_pad / kDeepMbWg));
-#define GDWS_DEEP_CASE(DT_, TW_, CS_) \
-    if (a.dtype == DT_ && t.TW == TW_ && t.cs == CS_) return launch_deep_instance<DT_, TW_, CS_>(p, grid, t.lds_bytes, s);
+    // a small launch is split over runs of row-block groups when the caller's workspace can take the partial sums
+    int S = deep_slices(sc, wgs);
+    const size_t need = (size_t)S * a.N * a.Ho * a.Wo * sc.m_blocks_pad * 32 * sizeof(float);
+    if (S > 1 && (!workspace || workspace_bytes < need || !sc.d_group_chan)) S = 1;
+    if (S > 1) {
+        p.groups_per_slice = (p.n_groups + S - 1) / S;
+        p.part = (float *)workspace;
+        p.part_slice = (int64_t)a.N * a.Ho * a.Wo * sc.m_blocks_pad * 32;
+    }
+    const dim3 grid((unsigned)((int64_t)p.tiles_x * p.tiles_y * tiles_n), (unsigned)(sc.m_blocks_pad / kDeepMbWg),
+                    (unsigned)S);
+    int rc = GDWS_EUNSUPPORTED;
+#define GDWS_DEEP_CASE(DT_, TW_, CS_)                                                                  \
+    if (a.dtype == DT_ && t.TW == TW_ && t.cs == CS_)                                                  \
+        rc = S > 1 ? launch_deep_instance<DT_, TW_, CS_, true>(p, grid, t.lds_bytes, s)                \
+                   : launch_deep_instance<DT_, TW_, CS_, false>(p, grid, t.lds_bytes, s);
     GDWS_DEEP_CASE(GDWS_BF16, 4, 256) GDWS_DEEP_CASE(GDWS_BF16, 4, 512) GDWS_DEEP_CASE(GDWS_BF16, 8, 256)
     GDWS_DEEP_CASE(GDWS_BF16, 8, 512) GDWS_DEEP_CASE(GDWS_F16, 4, 256) GDWS_DEEP_CASE(GDWS_F16, 4, 512)
     GDWS_DEEP_CASE(GDWS_F16, 8, 256) GDWS_DEEP_CASE(GDWS_F16, 8, 512)
 #undef GDWS_DEEP_CASE
-    return GDWS_EUNSUPPORTED;
+    if (rc != GDWS_OK || S == 1) return rc;
+    DeepFinishParams f;
+    f.part = p.part; f.part_slice = p.part_slice; f.slices = S; f.mpad = sc.m_blocks_pad * 32;
+    f.bias = sc.d_bias_pad; f.residual = p.residual; f.y = p.y; f.relu = p.relu; f.pool = p.pool;
+    f.N = a.N; f.M = a.M; f.Ho = a.Ho; f.Wo = a.Wo; f.Hp = p.Hp; f.Wp = p.Wp;
+    const int64_t outs = (int64_t)a.N * (a.pool ? p.Hp * p.Wp * 4 : a.Ho * a.Wo) * (a.M / 8);
+    if (outs == 0) return GDWS_OK;
+    const dim3 fgrid((unsigned)((outs + 255) / 256));
+    if (a.dtype == GDWS_BF16) gdws_deep_finish_kernel<GDWS_BF16><<<fgrid, 256, 0, s>>>(f);
+    else gdws_deep_finish_kernel<GDWS_F16><<<fgrid, 256, 0, s>>>(f);
+    GDWS_HIP_CHECK(hipGetLastError());
+    return GDWS_OK;
 }
 
 }  // namespace gdws

@@ -475,6 +475,11 @@ DEEP = [(64, 264, 4, 4, 264), (128, 256, 2, 2, 512), (32, 512, 7, 7, 256), (40, 
         (33, 200, 5, 6, 320), (70, 512, 4, 4, 512)]
 
 
+# the same kernel on a batch of one or two images: the launch is split over runs of row blocks, partial sums through the
+# workspace (gdws_workspace_bytes is then non-zero for the fused path), a second kernel adds them up
+DEEP += [(1, 512, 4, 4, 512), (2, 256, 2, 2, 512), (1, 264, 8, 8, 264), (3, 384, 7, 7, 256), (1, 136, 1, 5, 256)]
+
+
 @pytest.mark.parametrize("residual", [False, True])
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("case", range(len(DEEP)))
@@ -802,3 +807,34 @@ def test_backward(case, dtype, layout):
     gd.gdws_backward(plan, xd, dyd, N, H, W, dx=dx, workspace=ws)
     torch.cuda.synchronize()
     assert (d_pw == 7.0).all() and (from_device(dx, dtype, layout) == dxh).all()
+
+
+@pytest.mark.gpu
+def test_split_launch_needs_its_workspace_and_matches_the_unsplit_one():
+    """A batch-1 deep layer: with the workspace the fused path asks for, the launch is split over row blocks; without
+    it the same call still works (unsplit).  Both agree with the oracle; the split one is repeatable bit for bit."""
+    N, C, H, W, M = 1, 512, 4, 4, 512
+    g = _g("u14", C, 6100)
+    G = int(g.sum())
+    x = rng.normal(6101, (N, C, H, W))
+    dw = rng.normal(6102, (G, 3, 3), std=0.2)
+    pw = rng.normal(6103, (M, G), std=0.2)
+    b = rng.normal(6104, (M,), std=0.1)
+    plan = gd.gdws_plan(gd.make_desc(C, M, 3, 1, 1, "bf16", "nhwc", True, True, False), g, dw=dw, pw=pw, bias=b)
+    nbytes = gd.gdws_workspace_bytes(plan, N, H, W, gd.MODE_FUSED)
+    assert nbytes > 0 and nbytes == gd.gdws_workspace_bytes(plan, N, H, W, gd.MODE_AUTO)
+    assert gd.gdws_workspace_bytes(plan, 256, H, W, gd.MODE_FUSED) == 0          # a full batch is not split
+    xd, x_exact = to_device(x, "bf16", "nhwc")
+    dwq, pwq = gd.gdws_plan_factors(plan)
+    ref = oracle.gdws_forward(x_exact, g, dwq, pwq, b, None, True, 1, 1)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    outs = []
+    for workspace in (ws, ws, None, ws[: nbytes - 16]):
+        y = empty_act(N, M, H, W, "bf16", "nhwc", fill=float("nan"))
+        gd.gdws_forward(plan, xd, y, N, H, W, workspace=workspace, mode=gd.MODE_FUSED)
+        torch.cuda.synchronize()
+        outs.append(from_device(y, "bf16", "nhwc"))
+        assert np.isfinite(outs[-1]).all() and rel_l2(outs[-1], ref) <= TOL["bf16"]
+    assert (outs[0] == outs[1]).all()
+    assert (outs[2] == outs[3]).all()                                            # both unsplit
+    assert rel_l2(outs[0], outs[2]) <= 4e-3                                       # same sums in another order
