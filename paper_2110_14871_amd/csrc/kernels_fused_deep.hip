@@ -455,8 +455,8 @@ int launch_deep_instance(const DeepParams &p, dim3 grid, size_t lds_bytes, hipSt
     return GDWS_OK;
 }
 
-constexpr int64_t kDeepSplitBelow = 64;    // workgroups below which a launch is split over runs of row-block groups
-constexpr int64_t kDeepSplitTarget = 128;  // ... into about this many workgroups
+constexpr int64_t kDeepSplitBelow = 192;   // workgroups below which a launch is split over runs of row-block groups
+constexpr int64_t kDeepSplitTarget = 256;  // ... into about this many workgroups
 
 struct DeepTile {
     int TW, TH, TN, cs;
