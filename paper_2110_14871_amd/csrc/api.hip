@@ -434,7 +434,8 @@ int plan_impl(const gdws_layer_desc_t *desc, const int32_t *g, const float *W, c
     if (!rc) rc = upload(&p->d_bias, p->bias);
     if (!rc && fused_shape_supported(desc->dtype, desc->layout, desc->K, desc->stride, desc->pad, C, M)) {
         build_fused_schedule(p->fused, desc->dtype, desc->stride, C, M, g, p->offsets.data(), p->dw.data(),
-                             p->pw.data(), desc->has_bias ? p->bias.data() : nullptr);
+                             p->pw.data(), desc->has_bias ? p->bias.data() : nullptr, false, 0,
+                             desc->layout == GDWS_NHWC);
         rc = upload(&p->fused.d_stage_tab, p->fused.stage_tab);
         if (!rc) rc = upload(&p->fused.d_records, p->fused.records);
         if (!rc) rc = upload(&p->fused.d_pwfrag, p->fused.pwfrag);

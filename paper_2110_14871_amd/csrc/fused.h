@@ -42,6 +42,7 @@ struct FusedSchedule {
     bool valid = false;
     bool gdw_only = false;   // depthwise stage alone: row blocks own whole groups of 8 intermediate channels, no
                              // pointwise fragments; only for layers that are a single stage
+    bool tap2 = false;       // depthwise stage with two taps of an 8-channel window per MFMA (else one tap of 16 channels)
     int stride = 1;
     bool big = false;        // stage size class: stride 1: 128 (else 64) channels, stride 2: 32 (else 16)
     int stage_channels = 0;  // input channels per LDS stage
@@ -71,12 +72,13 @@ struct FusedSchedule {
 };
 
 // Builds the host tables from the (already rounded) factors.  dw [G][9], pw [M][G], bias [M] or nullptr.
+// allow_tap2: the builder may choose the two-tap depthwise stage (kernel instances exist for NHWC).
 // deep_stage (0, 256 or 512): the schedule of the deep-layer kernel (kernels_fused_deep.hip) -- all input channels
 // are one stage of that many channels, the row blocks are padded with empty ones to a multiple of four and the
 // output channels to a multiple of 256.
 void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M, const int32_t *g,
                           const int32_t *offsets, const float *dw, const float *pw, const float *bias,
-                          bool gdw_only = false, int deep_stage = 0);
+                          bool gdw_only = false, int deep_stage = 0, bool allow_tap2 = false);
 
 struct FusedArgs {
     const void *x;

@@ -152,11 +152,19 @@ __device__ inline void load_chunk_nchw(const FusedParams &p, uint32_t *lds, int 
 // SELF (NHWC, layers whose input channels are one stage): no loader waves.  The workgroup is the four compute waves,
 // which first load the stage themselves; with half the waves per workgroup twice as many workgroups are resident per
 // CU for the same registers, and their prologues and epilogues overlap the others' arithmetic.
-template <int DTYPE, int TW, int STRIDE, bool BIG, int MB, bool NHWC, bool GDWONLY = false, int NPB = 2, bool SELF = false>
+// TAP2 (NHWC): the depthwise MFMA's K dimension holds two filter taps of an 8-channel window instead of one tap of a
+// 16-channel window -- K element 8 h + c is tap 2 i + h of window channel c in MFMA i, so the lanes' upper half
+// (h = 1) builds its A operand from the odd tap and reads its B operand at the odd tap's pixel.  Nine taps are five
+// MFMAs instead of nine, with five LDS reads per pixel block and no lane exchange; the price is that a row block's
+// rows must come from 8 input channels, so layers with few filters per channel need more row blocks.  The plan
+// chooses per layer (build_fused_schedule).
+template <int DTYPE, int TW, int STRIDE, bool BIG, int MB, bool NHWC, bool GDWONLY = false, int NPB = 2, bool SELF = false,
+          bool TAP2 = false>
 __global__ __launch_bounds__(SELF ? kComputeThreads : kThreads, (NPB == 1 && MB == 2) ? 4 : 1)  // (four waves per SIMD: 128 registers)
 void gdws_fused_kernel(FusedParams params)
 {
     static_assert(!SELF || NHWC, "workgroups without loader waves exist for the NHWC kernels");
+    static_assert(!TAP2 || (NHWC && !GDWONLY), "the two-tap depthwise stage exists for the fused NHWC kernels");
     constexpr int kWgThreads = SELF ? kComputeThreads : kThreads;
     static_assert(NPB == 2 || (NPB == 1 && NHWC), "128-pixel tiles exist for the NHWC kernels");
     static_assert(TW >= 8 || NHWC, "tiles four pixels wide exist for the NHWC kernels (NCHW stores 8 pixels of a row)");
@@ -291,7 +299,7 @@ void gdws_fused_kernel(FusedParams params)
         for (int pb = 0; pb < NPB; ++pb) {
             const int pp = wave * (32 * NPB) + pb * 32 + l32;
             const int tx = pp % TW, ty = (pp / TW) & (p.TH - 1), tn = (pp / TW) >> p.th_log2;
-            base[pb] = ((tn * p.IH + ty * STRIDE) * Gm::IW + tx * STRIDE) * Gm::PSW + lhi * 4;
+            base[pb] = ((tn * p.IH + ty * STRIDE) * Gm::IW + tx * STRIDE) * Gm::PSW + (TAP2 ? 0 : lhi * 4);
         }
 
         // accumulators start from the bias
@@ -349,10 +357,10 @@ void gdws_fused_kernel(FusedParams params)
 #pragma unroll
         for (int i = 0; i < 16; ++i) zero[i] = 0.f;
 
-        constexpr bool kShare = STRIDE == 1;
+        constexpr bool kShare = STRIDE == 1 && !TAP2;
         // LDS reads of the depthwise B operand run this many reads ahead
-        constexpr int kReads = NPB * (kShare ? 6 : 9);  // LDS reads per row block
-        constexpr int kDepth = NPB == 1 ? 3 : kReadAhead;
+        constexpr int kReads = NPB * (TAP2 ? 5 : kShare ? 6 : 9);  // LDS reads per row block
+        constexpr int kDepth = TAP2 ? 5 : NPB == 1 ? 3 : kReadAhead;
         static_assert(kReads % kDepth == 0, "queue slots line up across row blocks only if the depth divides the reads");
         u32x4_t bq[kDepth];
         bool fill = true;
@@ -361,6 +369,15 @@ void gdws_fused_kernel(FusedParams params)
         // the taps whose operand comes from LDS, in reading order (each for all pixel blocks): at stride 1 the left
         // and the right tap of each filter row (the middle one is derived from them), else all nine
         auto read_tap = [](int r) { return kShare ? 3 * (r / 2) + 2 * (r % 2) : r; };
+        // two-tap stage: the lane's tap of each of the five MFMAs (tap 8 stands alone: the upper half multiplies it by
+        // zero) as an LDS offset, and the byte selector that duplicates the lane's tap of a record dword
+        int toff[5];
+        uint32_t psel = 0;
+        if constexpr (TAP2) {
+#pragma unroll
+            for (int i = 0; i < 5; ++i) toff[i] = tap_offset(i == 4 ? 8 : lhi ? 2 * i + 1 : 2 * i);
+            psel = lhi ? 0x03020302u : 0x01000100u;
+        }
 
         for (int idx = 0; idx < p.n_rowblocks; ++idx) {
             const uint32_t ctrl = (uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]);
@@ -383,7 +400,8 @@ void gdws_fused_kernel(FusedParams params)
             auto read16 = [](const uint32_t *ptr) { return *(const u32x4_a8_t *)ptr; };
             if (fill) {
 #pragma unroll
-                for (int i = 0; i < kDepth; ++i) bq[i] = read16(src[i % NPB] + tap_offset(read_tap(i / NPB)));
+                for (int i = 0; i < kDepth; ++i)
+                    bq[i] = read16(src[i % NPB] + (TAP2 ? toff[i / NPB] : tap_offset(read_tap(i / NPB))));
             }
             fill = !chain;
 
@@ -404,7 +422,25 @@ void gdws_fused_kernel(FusedParams params)
                 const uint32_t dup = __builtin_amdgcn_perm(word, word, (tap & 1) ? 0x03020302u : 0x01000100u);
                 return u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
             };
-            if (kShare) {
+            if constexpr (TAP2) {
+#pragma unroll
+                for (int i5 = 0; i5 < 5; ++i5) {
+                    const uint32_t word = i5 < 4 ? ra[i5] : (rb[0] & 0xffffu);  // (tap 8's partner is zero)
+                    const uint32_t dup = __builtin_amdgcn_perm(word, word, psel);
+                    const u32x4_t a = u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
+#pragma unroll
+                    for (int pb = 0; pb < NPB; ++pb) {
+                        const int i = NPB * i5 + pb;  // position in the sequence of LDS reads
+                        t[pb] = Op::mfma(a, bq[i % kDepth], i5 == 0 ? zero : t[pb]);
+                        const int n = i + kDepth;     // the read that takes the freed queue slot
+                        if (n < kReads) {
+                            bq[i % kDepth] = read16(src[n % NPB] + toff[n / NPB]);
+                        } else {  // (read in vain when the next row block does not chain)
+                            bq[i % kDepth] = read16(src[n % NPB] + next_delta + toff[(n - kReads) / NPB]);
+                        }
+                    }
+                }
+            } else if (kShare) {
                 // Stride 1: the middle tap of a filter row is not read from LDS.  Its operand is, lane by lane, the
                 // left tap's operand of the next pixel or the right tap's of the previous one, both in registers of
                 // neighbouring lanes of the same 16-lane row: two DPP moves per dword (lanes 0-3 and 8-11 of a row
@@ -671,19 +707,20 @@ void gdws_fused_kernel(FusedParams params)
 }
 
 // One launcher per (dtype, stride); each lives in a source file of its own so that the instances compile in parallel.
-typedef int (*fused_launcher_t)(const FusedParams &p, int TW, bool big, int mb, bool nhwc, int npb, bool self,
+typedef int (*fused_launcher_t)(const FusedParams &p, int TW, bool big, int mb, bool nhwc, int npb, bool self, bool tap2,
                                 dim3 grid, size_t lds_bytes, hipStream_t s);
 // (mb = 0 selects the depthwise-only instances, NHWC; npb = 1, the 128-pixel-tile instances, exists for NHWC; self,
 // the workgroups without loader waves, for NHWC, stride 1, npb = 1 and mb = 0 or 2)
-int launch_fused_bf16_s1(const FusedParams &, int, bool, int, bool, int, bool, dim3, size_t, hipStream_t);
-int launch_fused_bf16_s2(const FusedParams &, int, bool, int, bool, int, bool, dim3, size_t, hipStream_t);
-int launch_fused_f16_s1(const FusedParams &, int, bool, int, bool, int, bool, dim3, size_t, hipStream_t);
-int launch_fused_f16_s2(const FusedParams &, int, bool, int, bool, int, bool, dim3, size_t, hipStream_t);
+int launch_fused_bf16_s1(const FusedParams &, int, bool, int, bool, int, bool, bool, dim3, size_t, hipStream_t);
+int launch_fused_bf16_s2(const FusedParams &, int, bool, int, bool, int, bool, bool, dim3, size_t, hipStream_t);
+int launch_fused_f16_s1(const FusedParams &, int, bool, int, bool, int, bool, bool, dim3, size_t, hipStream_t);
+int launch_fused_f16_s2(const FusedParams &, int, bool, int, bool, int, bool, bool, dim3, size_t, hipStream_t);
 
-template <int DTYPE, int TW, int STRIDE, bool BIG, int MB, bool NHWC, bool GDWONLY = false, int NPB = 2, bool SELF = false>
+template <int DTYPE, int TW, int STRIDE, bool BIG, int MB, bool NHWC, bool GDWONLY = false, int NPB = 2, bool SELF = false,
+          bool TAP2 = false>
 int launch_instance(const FusedParams &p, dim3 grid, size_t lds_bytes, hipStream_t s)
 {
-    auto kern = gdws_fused_kernel<DTYPE, TW, STRIDE, BIG, MB, NHWC, GDWONLY, NPB, SELF>;
+    auto kern = gdws_fused_kernel<DTYPE, TW, STRIDE, BIG, MB, NHWC, GDWONLY, NPB, SELF, TAP2>;
     static bool raised = false;  // one flag per kernel instance
     if (!raised) {
         GDWS_HIP_CHECK(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
@@ -695,9 +732,28 @@ int launch_instance(const FusedParams &p, dim3 grid, size_t lds_bytes, hipStream
 }
 
 template <int DTYPE, int STRIDE>
-int launch_dispatch(const FusedParams &p, int TW, bool big, int mb, bool nhwc, int npb, bool self, dim3 grid,
+int launch_dispatch(const FusedParams &p, int TW, bool big, int mb, bool nhwc, int npb, bool self, bool tap2, dim3 grid,
                     size_t lds_bytes, hipStream_t s)
 {
+    if (tap2) {  // (the two-tap depthwise stage: NHWC, both strides, with loader waves, or without for 64-channel workgroups)
+        if (!nhwc || mb == 0) return GDWS_EUNSUPPORTED;
+#define GDWS_CASE_T2(tw, bg, m, np, sf)                                                               \
+    if (TW == tw && big == bg && mb == m && npb == np && self == sf)                                  \
+        return launch_instance<DTYPE, tw, STRIDE, bg, m, true, false, np, sf, true>(p, grid, lds_bytes, s);
+#define GDWS_CASES_T2(tw)                                                                             \
+    GDWS_CASE_T2(tw, false, 2, 2, false) GDWS_CASE_T2(tw, false, 4, 2, false) GDWS_CASE_T2(tw, true, 2, 2, false)   \
+    GDWS_CASE_T2(tw, true, 4, 2, false) GDWS_CASE_T2(tw, false, 2, 1, false) GDWS_CASE_T2(tw, false, 4, 1, false)   \
+    GDWS_CASE_T2(tw, true, 2, 1, false) GDWS_CASE_T2(tw, true, 4, 1, false)
+        GDWS_CASES_T2(4) GDWS_CASES_T2(8) GDWS_CASES_T2(16) GDWS_CASES_T2(32)
+        if constexpr (STRIDE == 1) {
+            GDWS_CASE_T2(4, false, 2, 1, true) GDWS_CASE_T2(4, true, 2, 1, true) GDWS_CASE_T2(8, false, 2, 1, true)
+            GDWS_CASE_T2(8, true, 2, 1, true) GDWS_CASE_T2(16, false, 2, 1, true) GDWS_CASE_T2(16, true, 2, 1, true)
+            GDWS_CASE_T2(32, false, 2, 1, true) GDWS_CASE_T2(32, true, 2, 1, true)
+        }
+#undef GDWS_CASES_T2
+#undef GDWS_CASE_T2
+        return GDWS_EUNSUPPORTED;
+    }
     if constexpr (STRIDE == 1) {
         if (self) {
 #define GDWS_CASE_SELF(tw, bg)                                                                        \

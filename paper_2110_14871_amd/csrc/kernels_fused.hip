@@ -96,9 +96,38 @@ TileChoice choose_tile(int Ho, int Wo, int stride, int C, int mb, bool nhwc, boo
 
 }  // namespace
 
+namespace {
+
+// Row blocks a layer is cut into when a row block's rows must come from `window` input channels (the greedy cut of
+// build_fused_schedule, counted only).
+int count_row_blocks(int C, int stage_channels, const int32_t *offsets, int window)
+{
+    int n = 0;
+    for (int c0 = 0; c0 < C; c0 += stage_channels) {
+        const int cnt = std::min(stage_channels, C - c0), cfill = (cnt + 15) & ~15;
+        int c = c0;  // channel of the next row
+        int left = c < c0 + cnt ? offsets[c + 1] - offsets[c] : 0;
+        auto skip_empty = [&]() { while (c < c0 + cnt && left == 0) { ++c; left = c < c0 + cnt ? offsets[c + 1] - offsets[c] : 0; } };
+        skip_empty();
+        while (c < c0 + cnt) {
+            const int cb0 = std::min(((c - c0) / kWindowAlign) * kWindowAlign, cfill - window);
+            int rows = 0;
+            while (c < c0 + cnt && rows < kRowBlock && c - c0 - cb0 < window) {
+                const int take = std::min(left, kRowBlock - rows);
+                rows += take; left -= take;
+                if (left == 0) { ++c; left = c < c0 + cnt ? offsets[c + 1] - offsets[c] : 0; skip_empty(); }
+            }
+            ++n;
+        }
+    }
+    return n;
+}
+
+}  // namespace
+
 void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M, const int32_t *g,
                           const int32_t *offsets, const float *dw, const float *pw, const float *bias, bool gdw_only,
-                          int deep_stage)
+                          int deep_stage, bool allow_tap2)
 {
     (void)g;
     const int G = offsets[C];
@@ -112,6 +141,18 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
     s.buffers = sg.buffers;
     s.m_blocks = (M + 31) / 32;
     s.mb_per_wg = deep_stage ? 8 : s.m_blocks >= 3 ? 4 : 2;
+    // One tap of a 16-channel window per depthwise MFMA, or two taps of an 8-channel window (see the kernel): the
+    // second takes 5 instead of 9 depthwise MFMAs per row block and pixel block and about two thirds of the vector
+    // instructions, but may need more row blocks.  Row-block costs in MFMA slots (the pointwise stage is 2 per
+    // 32 output channels; the vector instructions of a row block counted as 6 and 4 slots: measured on the 64- and
+    // 128-channel workgroups).
+    s.tap2 = false;
+    if (allow_tap2 && !gdw_only && !deep_stage && G > 0) {
+        const int mbw = std::min(s.mb_per_wg, s.m_blocks);
+        const double c16 = 9 + 2 * mbw + 6, c8 = 5 + 2 * mbw + 4;
+        s.tap2 = count_row_blocks(C, sg.stage_channels, offsets, 8) * c8 < count_row_blocks(C, sg.stage_channels, offsets, kWindow) * c16;
+    }
+    const int window = s.tap2 ? 8 : kWindow;
     s.m_blocks_pad = (s.m_blocks + s.mb_per_wg - 1) / s.mb_per_wg * s.mb_per_wg;
     s.bias_pad.assign((size_t)s.m_blocks_pad * 32, 0.f);
     if (bias) std::copy(bias, bias + M, s.bias_pad.begin());
@@ -180,12 +221,12 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
             rb.stage = s.n_stages;
             // the 16-channel window starts at a multiple of 4 (8-byte aligned LDS reads) and stays inside the
             // zero-filled stage
-            rb.cb0 = std::min(((chan[j] - c0) / kWindowAlign) * kWindowAlign, cfill - kWindow);
+            rb.cb0 = std::min(((chan[j] - c0) / kWindowAlign) * kWindowAlign, cfill - window);
             int nrows = 0;
-            while (j < jend && nrows < kRowBlock && chan[j] - c0 - rb.cb0 < kWindow) rb.rows[nrows++] = j++;
+            while (j < jend && nrows < kRowBlock && chan[j] - c0 - rb.cb0 < window) rb.rows[nrows++] = j++;
             for (int r = nrows; r < kRowBlock; ++r) rb.rows[r] = -1;
             rb.own = 0;
-            rb.last_chunk = chunk_base + (rb.cb0 + kWindow - 1) / s.chunk_channels + 1;
+            rb.last_chunk = chunk_base + (rb.cb0 + window - 1) / s.chunk_channels + 1;
             rbs.push_back(rb);
         }
         s.stage_tab.push_back(c0);
@@ -246,7 +287,8 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
                 for (int d = 0; d < 4; ++d) qa[d] = (uint32_t)h[2 * d] | ((uint32_t)h[2 * d + 1] << 16);
                 qb[0] = h[8];
                 // this lane holds columns 8*half .. 8*half+7 of its row; the row's only column is the channel
-                const int pos = (chan[jr] - rb.c0 - rb.cb0) - 8 * (l >> 5);
+                // (two-tap stage: both halves of the lanes hold the same 8 channels, each for its own tap)
+                const int pos = (chan[jr] - rb.c0 - rb.cb0) - (s.tap2 ? 0 : 8 * (l >> 5));
                 if (pos >= 0 && pos < 8) sel = (uint32_t)(pos / 2) | ((pos & 1) ? 8u : 0u);
             }
             qb[0] |= (sel << 16) | (rb.own << 20);
@@ -358,7 +400,7 @@ int launch_fused(const FusedArgs &a, hipStream_t s)
     // LDS then holds three or more workgroups per CU.
     const bool self = nhwc && a.stride == 1 && npb == 1 && (mb == 2 || sc.gdw_only) && sc.n_stages == 1 &&
                       tc.lds_bytes <= (size_t)kMaxLds / 3;
-    return fn(p, tc.TW, sc.big, sc.gdw_only ? 0 : mb, nhwc, npb, self, grid, tc.lds_bytes, s);
+    return fn(p, tc.TW, sc.big, sc.gdw_only ? 0 : mb, nhwc, npb, self, sc.tap2, grid, tc.lds_bytes, s);
 }
 
 }  // namespace gdws

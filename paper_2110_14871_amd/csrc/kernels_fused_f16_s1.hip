@@ -4,10 +4,10 @@
 namespace gdws {
 namespace fusedk {
 
-int launch_fused_f16_s1(const FusedParams &p, int TW, bool big, int mb, bool nhwc, int npb, bool self,
+int launch_fused_f16_s1(const FusedParams &p, int TW, bool big, int mb, bool nhwc, int npb, bool self, bool tap2,
                           dim3 grid, size_t lds_bytes, hipStream_t s)
 {
-    return launch_dispatch<GDWS_F16, 1>(p, TW, big, mb, nhwc, npb, self, grid, lds_bytes, s);
+    return launch_dispatch<GDWS_F16, 1>(p, TW, big, mb, nhwc, npb, self, tap2, grid, lds_bytes, s);
 }
 
 }  // namespace fusedk
