@@ -838,3 +838,34 @@ def test_split_launch_needs_its_workspace_and_matches_the_unsplit_one():
     assert (outs[0] == outs[1]).all()
     assert (outs[2] == outs[3]).all()                                            # both unsplit
     assert rel_l2(outs[0], outs[2]) <= 4e-3                                       # same sums in another order
+
+
+@pytest.mark.gpu
+def test_error_codes_of_the_later_entry_points():
+    """gdws_singular_values_device and gdws_backward refuse what they cannot do, with the documented codes."""
+    w = torch.zeros(4, 2, 9, 9, dtype=torch.float32, device="cuda")
+    sigma = torch.zeros(2, 4, dtype=torch.float64, device="cuda")
+    with pytest.raises(gd.GdwsError) as e:
+        gd.gdws_singular_values_device(w, sigma)                    # K = 9: beyond the kernel's 7 x 7
+    assert e.value.code == -3
+    with pytest.raises(gd.GdwsError) as e:
+        gd.gdws_singular_values_device(w[:, :, :3, :3].contiguous(), None)
+    assert e.value.code == -2
+    g = np.ones(8, np.int32)
+    plan = gd.gdws_plan(gd.make_desc(8, 16, 3, 1, 1, "f16", "nhwc"), g, dw=np.ones((8, 3, 3), np.float32),
+                        pw=np.ones((16, 8), np.float32))
+    x = torch.zeros(1, 6, 6, 8, device="cuda", dtype=torch.float16)
+    dy = torch.zeros(1, 6, 6, 16, device="cuda", dtype=torch.float16)
+    ws = torch.empty(gd.gdws_backward_workspace_bytes(plan, 1, 6, 6), dtype=torch.uint8, device="cuda")
+    with pytest.raises(gd.GdwsError) as e:
+        gd.gdws_backward(plan, x, None, 1, 6, 6, dx=torch.empty_like(x), workspace=ws)
+    assert e.value.code == -2
+    with pytest.raises(gd.GdwsError) as e:
+        gd.gdws_backward(plan, x, dy, 1, 6, 6, dx=torch.empty_like(x), workspace=None)
+    assert e.value.code == -4
+    with pytest.raises(gd.GdwsError) as e:
+        gd.gdws_backward(plan, x, dy, 0, 6, 6, dx=torch.empty_like(x), workspace=ws)
+    assert e.value.code == -1
+    assert gd.gdws_backward_workspace_bytes(plan, 0, 6, 6) == 0
+    gd.gdws_backward(plan, x, dy, 1, 6, 6, workspace=ws)              # nothing asked for: still a valid call
+    torch.cuda.synchronize()
