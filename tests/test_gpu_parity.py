@@ -869,3 +869,23 @@ def test_error_codes_of_the_later_entry_points():
     assert gd.gdws_backward_workspace_bytes(plan, 0, 6, 6) == 0
     gd.gdws_backward(plan, x, dy, 1, 6, 6, workspace=ws)              # nothing asked for: still a valid call
     torch.cuda.synchronize()
+
+
+# layers with three to nine filters per channel: the plan takes the depthwise stage with two taps per MFMA (8-channel
+# windows).  256- and 128-pixel tiles, 64- and 128-channel workgroups, with and without loader waves, one and several
+# input stages, stride 2, four-pixel tile rows, ragged sizes, channels with no filter in between.
+TWO_TAP = [(3, 128, 16, 16, 128, 1, "u39"), (2, 64, 32, 32, 64, 1, "u35"), (2, 32, 17, 19, 40, 1, "u39"),
+           (2, 256, 8, 8, 256, 1, "u36"), (2, 64, 12, 12, 96, 2, "u39"), (70, 64, 4, 4, 256, 1, "u39"),
+           (2100, 16, 4, 4, 32, 1, "u39"), (1, 136, 10, 12, 136, 1, "u09"), (5, 24, 9, 9, 72, 2, "u39"),
+           (300, 64, 8, 8, 64, 1, "all9")]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("residual", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("case", range(len(TWO_TAP)))
+def test_two_tap_layers(case, dtype, residual):
+    N, C, H, W, M, stride, rule = TWO_TAP[case]
+    g = _g(rule, C, 5300 + case)
+    check_layer(5310 + 10 * case, N, C, H, W, M, 3, stride, 1, g, dtype, "nhwc", gd.MODE_FUSED, bias=True,
+                residual=residual, relu=(case % 2 == 0))
