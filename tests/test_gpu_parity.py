@@ -889,3 +889,34 @@ def test_two_tap_layers(case, dtype, residual):
     g = _g(rule, C, 5300 + case)
     check_layer(5310 + 10 * case, N, C, H, W, M, 3, stride, 1, g, dtype, "nhwc", gd.MODE_FUSED, bias=True,
                 residual=residual, relu=(case % 2 == 0))
+
+
+@pytest.mark.gpu
+def test_one_plan_on_two_streams_at_once():
+    """A plan is immutable: forwards on different streams with their own buffers may overlap.  Same results, bit for
+    bit, as one after the other (general kernel, deep-layer kernel and its split launch with separate workspaces)."""
+    for (N, C, H, W, M) in ((64, 128, 16, 16, 128), (48, 512, 4, 4, 512), (1, 512, 4, 4, 512)):
+        g = _g("u14", C, 6200)
+        G = int(g.sum())
+        dw = rng.normal(6201, (G, 3, 3), std=0.2)
+        pw = rng.normal(6202, (M, G), std=0.2)
+        plan = gd.gdws_plan(gd.make_desc(C, M, 3, 1, 1, "bf16", "nhwc", True), g, dw=dw, pw=pw)
+        nbytes = max(1, gd.gdws_workspace_bytes(plan, N, H, W, gd.MODE_FUSED))
+        xs = [to_device(rng.normal(6210 + k, (N, C, H, W)), "bf16", "nhwc")[0] for k in range(2)]
+        wss = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+        seq = []
+        for k in range(2):
+            y = empty_act(N, M, H, W, "bf16", "nhwc", fill=float("nan"))
+            gd.gdws_forward(plan, xs[k], y, N, H, W, workspace=wss[k], mode=gd.MODE_FUSED)
+            torch.cuda.synchronize()
+            seq.append(y.clone())
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        ys = [empty_act(N, M, H, W, "bf16", "nhwc", fill=float("nan")) for _ in range(2)]
+        torch.cuda.synchronize()
+        for rep in range(20):                      # interleaved launches: the two streams' kernels overlap on the chip
+            for k in range(2):
+                gd.gdws_forward(plan, xs[k], ys[k], N, H, W, workspace=wss[k], mode=gd.MODE_FUSED, stream=streams[k])
+        for st in streams:
+            st.synchronize()
+        for k in range(2):
+            assert torch.equal(ys[k].view(torch.int16), seq[k].view(torch.int16))
