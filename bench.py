@@ -35,10 +35,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=0, help="timed steps (0 = the workload's default)")
     ap.add_argument("--warmup", type=int, default=-1, help="untimed steps before them (-1 = the workload's default)")
     ap.add_argument("--workload", default="config2",
-                    choices=["config2", "config2_g9", "config2_g1", "config2_dense", "config2_backward"] + sorted(NETWORKS),
+                    choices=["config1", "config2", "config2_g9", "config2_g1", "config2_dense", "config2_backward"] + sorted(NETWORKS),
                     help="config2 (default, the headline layer), its two sub-runs, the standard convolution it "
                          "approximates (config2_dense: conv_dense_forward on the same shape), the layer's backward "
-                         "pass (config2_backward: gdws_backward, all four gradients), or a network-shaped "
+                         "pass (config2_backward: gdws_backward, all four gradients), the small fp32 layer at batch 1 "
+                         "(config1: latency of one call), or a network-shaped "
                          "workload (VGG-16 fp16 batch 256, ResNet-18 bf16 batch 512, WRN-28-4 bf16 batch 256 at 32x32; "
                          "ResNet-50 bf16 batch 128 at 224x224)")
     ap.add_argument("--batch", type=int, default=0, help="network workloads: batch size (0 = the workload's own); "
@@ -280,6 +281,60 @@ def run_backward(a):
                                "rel_l2_dx_gpu_vs_oracle": err}
     print(json.dumps(out))
 
+def run_config1(a):
+    """Configuration 1 (fp32, N = 1, 16 -> 32 channels, 32 x 32, NCHW): the latency of one call, which at this size is a
+    launch latency; priced against the fp32 vector peak only to give the line its roofline object."""
+    import torch
+    import paper_2110_14871_amd as gd
+    import workloads
+    from gpu_util import empty_act, from_device, rel_l2, to_device
+
+    torch.cuda.set_device(0)
+    steps = a.steps or 2000
+    warmup = a.warmup if a.warmup >= 0 else 200
+    c = workloads.config1()
+    N, C, H, W, M, K = c["N"], c["C"], c["H"], c["W"], c["M"], c["K"]
+    mode = {"auto": gd.MODE_AUTO, "fused": gd.MODE_FUSED, "unfused": gd.MODE_UNFUSED}[a.mode]
+    plan = gd.gdws_plan(gd.make_desc(C, M, K, 1, 1, "f32", "nchw"), c["g"], W=c["Wt"])
+    G = int(c["g"].sum())
+    stream = torch.cuda.Stream()
+    xd, x_exact = to_device(c["X"], "f32", "nchw")
+    y = empty_act(N, M, H, W, "f32", "nchw")
+    ws = torch.empty(max(1, gd.gdws_workspace_bytes(plan, N, H, W, mode)), dtype=torch.uint8, device="cuda")
+
+    def step(k):
+        gd.gdws_forward(plan, xd, y, N, H, W, workspace=ws, mode=mode, stream=stream)
+
+    stepper = Stepper(gd, step, 1, stream, False)     # call by call: the figure is the latency of a call
+    clock_ramp(stepper, a.ramp_ms)
+    wall_ms, dev_ms = timed(stepper, steps, warmup)
+    flops = 2.0 * N * H * W * G * (K * K + M)
+    tflops = flops / (dev_ms * 1e-3) / 1e12
+    fused = gd.gdws_workspace_bytes(plan, N, H, W, mode) == 0
+    out = {
+        "metric": "GDWS layer images/sec at batch 1 (configuration 1, latency)", "value": N / (wall_ms * 1e-3),
+        "unit": "images/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config1: GDWS layer fp32 N=1 C=16 32x32 K=3 M=32 G={G}", "layout": "nchw",
+                   "path": "fused (vector-ALU kernel)" if fused else "unfused (direct depthwise + fp32 MFMA pointwise)",
+                   "launch": "eager, one call per step"},
+        "roofline": {"bound": "alu", "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / FP32_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel_ms": dev_ms, "flops": flops},
+    }
+    if not a.no_cpu_baseline:
+        import oracle
+        dw, pw = gd.gdws_plan_factors(plan)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 200
+        for _ in range(reps):
+            ref = oracle.gdws_forward(x_exact, c["g"], dw, pw, stride=1, pad=1, threads=1)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": reps / dt, "unit": "images/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the one image, {reps} passes of the fp64 loops on one thread, {dt:.2f} s",
+                               "rel_l2_gpu_vs_oracle": rel_l2(from_device(y, "f32", "nchw"), ref)}
+    print(json.dumps(out))
+
 
 def main():
     a = parse()
@@ -291,6 +346,8 @@ def main():
         return run_network(a)
     if a.workload == "config2_backward":
         return run_backward(a)
+    if a.workload == "config1":
+        return run_config1(a)
 
     import numpy as np
     import torch
