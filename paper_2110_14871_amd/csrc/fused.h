@@ -10,9 +10,10 @@
 //
 // Both stages of the layer run on the matrix cores.  The intermediate channels are cut, in channel
 // order, into "row blocks" of at most 32 whose input channels fit one 16-channel window.  For a
-// row block the depthwise stage is nine MFMAs per 32 pixels, one per filter tap: A is the 32 x 16
-// matrix that holds tap (u,v) of intermediate channel j in column chan_of[j] (one non-zero per row,
-// built in registers from a per-lane tap value and a per-lane mask), B is the 16-channel slice of
+// row block the depthwise stage is, per 32 pixels, one matrix instruction per filter tap or pair of taps: A
+// is the 32 x 16 matrix that holds tap (u,v) of intermediate channel j in column chan_of[j] (one non-zero per
+// row, built in registers from a per-lane tap value and a per-lane mask; two taps side by side are the 2:4
+// sparse operand of v_smfmac_f32_32x32x32), B is the 16-channel slice of
 // the input tile shifted by (u,v), read straight from LDS.  The 32 x 32 fp32 result is rounded to the
 // storage type in the lane that holds it and is, without any data movement, the B operand of the
 // pointwise MFMAs (the pointwise weights are packed at plan time in the matching K order).
@@ -25,6 +26,18 @@ namespace gdws {
 
 constexpr int kRowBlock = 32;  // intermediate channels per row block
 constexpr int kWindow = 16;    // input channels one row block may draw from (K of the depthwise MFMA)
+
+// LDS layout of the input tile: pixel-major, a pixel's stage channels followed by padding, and every tile row followed
+// by lds_row_pad dwords.  A window starts at a multiple of four channels, so the depthwise B operand (16 bytes per lane)
+// is read as a pair of 8-byte halves.  Measured with a read-only loop (all four waves of a CU reading, 1 KB per
+// wave-read): a pixel stride of 4 modulo 32 dwords (16 bytes of padding) serves such a read in 64 cycles, whatever the
+// row pad; a stride of 2 modulo 4 dwords (8 bytes of padding) in 32 cycles when the 32 pixels of a block are two rows
+// of 16 or one of 32, and with the row pad below also when they are four rows of 8 or eight of 4.  (Aligned 16-byte
+// reads reach 20 cycles with a row pad of 56 dwords, but need windows at multiples of eight channels, which costs
+// more row blocks than the reads save.)  At stride 2 neighbouring lanes are two pixels apart and no padding does
+// better than 64 cycles: those tiles keep 16 bytes of padding (aligned LDS writes).
+constexpr int lds_pixel_dwords(int stage_channels, int stride) { return stage_channels / 2 + (stride == 1 ? 2 : 4); }
+constexpr int lds_row_pad(int tw, int stride) { return stride == 1 && tw <= 8 ? 28 : 0; }
 
 // Record of a row block, per lane: six dwords in two arrays (16-byte and 8-byte loads).
 //   a[0..3]  taps 0..7 of the lane's row, two per dword
@@ -43,6 +56,8 @@ struct FusedSchedule {
     bool gdw_only = false;   // depthwise stage alone: row blocks own whole groups of 8 intermediate channels, no
                              // pointwise fragments; only for layers that are a single stage
     bool tap2 = false;       // depthwise stage with two taps of an 8-channel window per MFMA (else one tap of 16 channels)
+    bool sparse = false;     // records in the form of the sparse-MFMA depthwise stage (one tap of 16 channels, taps
+                             // paired): a[i] = taps 2i+1, 2i+2; b[0] = tap 0 | window column of the row << 16 | own << 20
     int stride = 1;
     bool big = false;        // stage size class: stride 1: 128 (else 64) channels, stride 2: 32 (else 16)
     int stage_channels = 0;  // input channels per LDS stage

@@ -3,11 +3,13 @@
 //
 // Depthwise stage of one row block (<= 32 intermediate channels drawing on a 16-channel window), for
 // 32 pixels:   T[j][p] = sum over taps (u,v) of  A_uv[j][c] * X[c][p + (u,v)]
-// A_uv has a single non-zero per row (tap (u,v) of filter j, in the column of its input channel); each
-// lane builds its 8-element slice of a row with a byte permute and four ANDs from the packed taps and
-// four masks that are fixed for the row block.  X[.][p + (u,v)] is a 16-byte LDS read: the input
-// tile is stored pixel-major, so the 8 consecutive channels a lane needs are contiguous and a tap
-// is just an address offset.  Accumulation is fp32 inside v_mfma_f32_32x32x16.
+// A_uv has a single non-zero per row (tap (u,v) of filter j, in the column of its input channel), so two taps
+// side by side are a 32 x 32 matrix with at most one non-zero in every group of four columns: the operand form of
+// the 2:4 sparse MFMA (v_smfmac_f32_32x32x32), which multiplies two taps in the time a dense MFMA takes for one.
+// Nine taps are one dense MFMA and four sparse ones.  Each lane builds its slice of a row with a byte permute and
+// four ANDs from the packed taps and four masks that are fixed for the row block.  X[.][p + (u,v)] is a 16-byte
+// LDS read: the input tile is stored pixel-major, so the 8 consecutive channels a lane needs are contiguous and a
+// tap is just an address offset.  Accumulation is fp32 inside the matrix instructions.
 //
 // Pointwise stage: the fp32 tile is rounded to the storage type (nearest even) where it sits; in the
 // MFMA register layout a lane then already holds what the B operand of the next MFMA expects, in a
@@ -34,6 +36,9 @@ namespace gdws {
 namespace fusedk {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) __bf16 bf16x16_t;
+typedef __attribute__((ext_vector_type(16))) _Float16 f16x16_t;
+typedef __attribute__((ext_vector_type(8))) uint32_t u32x8_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
@@ -64,6 +69,14 @@ template <> struct half_ops<GDWS_BF16> {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
                                                        c, 0, 0, 0);
     }
+    // D += A B with A 32 x 32 in the 2:4 compressed form (eight values per lane and two index bits for each) and
+    // B 32 x 32 dense: lane (column n, half hb) holds K elements 8 hb .. 8 hb + 7 (b0) and 16 + 8 hb .. 23 + 8 hb (b1)
+    __device__ static f32x16_t smfmac(u32x4_t a, u32x4_t b0, u32x4_t b1, f32x16_t c, int index)
+    {
+        const u32x8_t b = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+        return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x16_t, b),
+                                                         c, index, 0, 0);
+    }
     __device__ static float widen(uint16_t h) { return bf16_to_float(h); }
 };
 
@@ -78,6 +91,12 @@ template <> struct half_ops<GDWS_F16> {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c,
                                                       0, 0, 0);
     }
+    __device__ static f32x16_t smfmac(u32x4_t a, u32x4_t b0, u32x4_t b1, f32x16_t c, int index)
+    {
+        const u32x8_t b = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+        return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x16_t, b),
+                                                        c, index, 0, 0);
+    }
     __device__ static float widen(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 };
 
@@ -88,6 +107,7 @@ __device__ inline float relu_bits(float v)
     const int b = __builtin_bit_cast(int, v);
     return __builtin_bit_cast(float, b > 0 ? b : 0);
 }
+
 
 struct FusedParams {
     const uint16_t *x;
@@ -116,8 +136,9 @@ template <int TW, int STRIDE, bool BIG> struct Geom {
     static constexpr int SC = STRIDE == 1 ? (BIG ? 128 : 64) : (BIG ? 32 : 16);  // channels per stage
     static constexpr int CC = STRIDE == 1 ? 32 : 16;    // channels per chunk
     static constexpr int NCH = SC / CC;                 // chunks per stage, at most
-    static constexpr int PSW = SC / 2 + 4;              // dwords per pixel (16 bytes of padding: conflict-free b128 reads)
+    static constexpr int PSW = lds_pixel_dwords(SC, STRIDE);  // dwords per pixel
     static constexpr int IW = (TW - 1) * STRIDE + 3;    // input columns per tile row
+    static constexpr int RP = IW * PSW + lds_row_pad(TW, STRIDE);  // dwords per tile row
 };
 
 // NCHW loader of one chunk (channels [cb, cb + cn) of the stage buffer, filled with zeros past c_count): a thread
@@ -137,7 +158,7 @@ __device__ inline void load_chunk_nchw(const FusedParams &p, uint32_t *lds, int 
         const int n = n0 + tn, gy = ty0 * STRIDE - 1 + iy, gx0 = tx0 * STRIDE - 1;
         const bool row_in = n < p.N && gy >= 0 && gy < p.H && cs < c_count;
         const uint16_t *src = p.x + (((int64_t)n * p.C + c_begin + cs) * p.H + gy) * p.W + gx0;
-        uint16_t *dst = lds16 + (r * Gm::IW) * (Gm::PSW * 2) + cs;
+        uint16_t *dst = lds16 + r * (Gm::RP * 2) + cs;
 #pragma unroll 6
         for (int ix = 0; ix < Gm::IW; ++ix) {
             const int gx = gx0 + ix;
@@ -214,6 +235,7 @@ void gdws_fused_kernel(FusedParams params)
             // returns zeros: the padding costs no branch.  A chunk is then nent loads and nent LDS writes.
             constexpr uint32_t kOutside = 0x80000000u;
             uint32_t voff[kMaxEnt];
+            uint32_t loff[kMaxEnt];  // dword offset of the entry's pixel in a stage buffer
             // walk over the thread's pixels: (column, row, image) inside the input tile, advanced by PSTEP pixels
             int ix = pix0 % Gm::IW, iy, tn;
             {
@@ -225,8 +247,9 @@ void gdws_fused_kernel(FusedParams params)
             while (diy >= p.IH) { diy -= p.IH; ++dtn; }
             const int gy0 = ty0 * STRIDE - 1, gx0 = tx0 * STRIDE - 1;
             const uint32_t c2 = (uint32_t)p.C * 2u;
-            auto next_offset = [&]() {
+            auto next_offset = [&](uint32_t &lds_off) {
                 const int n = n0 + tn, gy = gy0 + iy, gx = gx0 + ix;
+                lds_off = (uint32_t)((tn * p.IH + iy) * Gm::RP + ix * Gm::PSW);
                 const bool in = tn < p.TN && n < p.N && (unsigned)gy < (unsigned)p.H && (unsigned)gx < (unsigned)p.W;
                 // 24-bit multiplies: the host admits fewer than 2^24 input pixels
                 const uint32_t pixel = __umul24(__umul24(n, p.H) + gy, p.W) + gx;
@@ -237,7 +260,7 @@ void gdws_fused_kernel(FusedParams params)
                 return off;
             };
             const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, 0x00020000);
-            uint32_t *dst0 = lds + pix0 * Gm::PSW + q * 4;
+            uint32_t *dst0 = lds + q * 4;
             // In the first stage the offsets are worked out as the first chunk's loads go out, so that the first of
             // them is in flight after a few dozen instructions.
             auto run_stage = [&](int st, int c_begin, int c_count, auto first) {
@@ -252,7 +275,7 @@ void gdws_fused_kernel(FusedParams params)
 #pragma unroll
                     for (int k = 0; k < kMaxEnt; ++k)
                         if (k < nent) {
-                            if (first && ch == 0) voff[k] = next_offset();
+                            if (first && ch == 0) voff[k] = next_offset(loff[k]);
                             v[ch & 1][k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[k] | gone,
                                                                              (c_begin + ch * Gm::CC) * 2, 0);
                         }
@@ -265,7 +288,7 @@ void gdws_fused_kernel(FusedParams params)
                         // the stage buffer has room for the pixels of the last pass that lie past the tile
 #pragma unroll
                         for (int k = 0; k < kMaxEnt; ++k)
-                            if (k < nent) *(u32x4_t *)(dst + k * PSTEP * Gm::PSW + ch * (Gm::CC / 2)) = v[ch & 1][k];
+                            if (k < nent) *(u32x4_a8_t *)(dst + loff[k] + ch * (Gm::CC / 2)) = v[ch & 1][k];
                         __syncthreads();  // chunk ch of stage st is in LDS
                         if (ch + 2 < Gm::NCH && ch + 2 < nch) issue(ch + 2);
                     }
@@ -299,7 +322,7 @@ void gdws_fused_kernel(FusedParams params)
         for (int pb = 0; pb < NPB; ++pb) {
             const int pp = wave * (32 * NPB) + pb * 32 + l32;
             const int tx = pp % TW, ty = (pp / TW) & (p.TH - 1), tn = (pp / TW) >> p.th_log2;
-            base[pb] = ((tn * p.IH + ty * STRIDE) * Gm::IW + tx * STRIDE) * Gm::PSW + (TAP2 ? 0 : lhi * 4);
+            base[pb] = (tn * p.IH + ty * STRIDE) * Gm::RP + tx * STRIDE * Gm::PSW + (TAP2 ? 0 : lhi * 4);
         }
 
         // accumulators start from the bias
@@ -365,19 +388,20 @@ void gdws_fused_kernel(FusedParams params)
         u32x4_t bq[kDepth];
         bool fill = true;
 
-        auto tap_offset = [](int tap) { return ((tap / 3) * Gm::IW + (tap % 3)) * Gm::PSW; };
+        auto tap_offset = [](int tap) { return (tap / 3) * Gm::RP + (tap % 3) * Gm::PSW; };
         // the taps whose operand comes from LDS, in reading order (each for all pixel blocks): at stride 1 the left
         // and the right tap of each filter row (the middle one is derived from them), else all nine
         auto read_tap = [](int r) { return kShare ? 3 * (r / 2) + 2 * (r % 2) : r; };
         // two-tap stage: the lane's tap of each of the five MFMAs (tap 8 stands alone: the upper half multiplies it by
         // zero) as an LDS offset, and the byte selector that duplicates the lane's tap of a record dword
         int toff[5];
-        uint32_t psel = 0;
         if constexpr (TAP2) {
 #pragma unroll
             for (int i = 0; i < 5; ++i) toff[i] = tap_offset(i == 4 ? 8 : lhi ? 2 * i + 1 : 2 * i);
-            psel = lhi ? 0x03020302u : 0x01000100u;
         }
+        // the byte selector that duplicates the lane's tap of a record dword (lower half of the lanes: the first tap
+        // of the pair, upper half: the second)
+        const uint32_t psel = lhi ? 0x03020302u : 0x01000100u;
 
         for (int idx = 0; idx < p.n_rowblocks; ++idx) {
             const uint32_t ctrl = (uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]);
@@ -390,9 +414,8 @@ void gdws_fused_kernel(FusedParams params)
             if constexpr (!SELF) {  // (without loader waves the whole stage is in LDS before the first row block)
                 for (int w = 0; w < nwait; ++w) __syncthreads();  // the chunks the window lies in have landed
             }
-            // A window starts at a multiple of four channels, so a lane's 16 bytes are 8-byte aligned (the compiler
-            // then reads them as a pair of 8-byte halves; at a 16-byte aligned address that is as fast as one
-            // 16-byte read, at the others the hardware takes a slower path).
+            // A window starts at a multiple of four channels, so a lane's 16 bytes are 8-byte aligned: a pair of
+            // 8-byte reads in one instruction.
             const uint32_t *src[NPB];
 #pragma unroll
             for (int pb = 0; pb < NPB; ++pb) src[pb] = buf + base[pb] + win_off;
@@ -403,26 +426,20 @@ void gdws_fused_kernel(FusedParams params)
                 for (int i = 0; i < kDepth; ++i)
                     bq[i] = read16(src[i % NPB] + (TAP2 ? toff[i / NPB] : tap_offset(read_tap(i / NPB))));
             }
-            fill = !chain;
+            fill = SELF ? false : !chain;  // (without loader waves the stage is complete: every row block reads ahead)
 
-            // masks: which of the lane's four A dwords, and which half of it, holds the row's column
-            const uint32_t sel = rb[0] >> 16;
-            const uint32_t hm = (sel & 8) ? 0xFFFF0000u : 0x0000FFFFu;
-            uint32_t m[4];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) m[d] = (sel & 7) == (uint32_t)d ? hm : 0u;
-
-            // ---- depthwise: two 32-pixel blocks x nine taps; each block is rounded to the storage type when
+            // ---- depthwise: NPB 32-pixel blocks x nine taps; each block is rounded to the storage type when
             // done: register i of a lane pairs up as K element i % 8 of K-step i / 8 ----
-            // The two blocks advance together, tap by tap, so that the A operand of a tap is built once.
+            // The blocks advance together, tap by tap, so that the A operand of a tap is built once.
             f32x16_t t[NPB];
             u32x4_t tb[NPB][2];
-            auto a_operand = [&](int tap) {
-                const uint32_t word = tap == 8 ? rb[0] : ra[tap / 2];
-                const uint32_t dup = __builtin_amdgcn_perm(word, word, (tap & 1) ? 0x03020302u : 0x01000100u);
-                return u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
-            };
             if constexpr (TAP2) {
+                // masks: which of the lane's four A dwords, and which half of it, holds the row's column
+                const uint32_t sel = rb[0] >> 16;
+                const uint32_t hm = (sel & 8) ? 0xFFFF0000u : 0x0000FFFFu;
+                uint32_t m[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) m[d] = (sel & 7) == (uint32_t)d ? hm : 0u;
 #pragma unroll
                 for (int i5 = 0; i5 < 5; ++i5) {
                     const uint32_t word = i5 < 4 ? ra[i5] : (rb[0] & 0xffffu);  // (tap 8's partner is zero)
@@ -440,26 +457,51 @@ void gdws_fused_kernel(FusedParams params)
                         }
                     }
                 }
-            } else if (kShare) {
-                // Stride 1: the middle tap of a filter row is not read from LDS.  Its operand is, lane by lane, the
-                // left tap's operand of the next pixel or the right tap's of the previous one, both in registers of
-                // neighbouring lanes of the same 16-lane row: two DPP moves per dword (lanes 0-3 and 8-11 of a row
-                // take the former, lanes 4-7 and 12-15 the latter, so no lane reaches across a tile row's end).
-                // Reads of a filter row, in order: left tap of block 0, of block 1, right tap of block 0, of block 1.
+            } else {
+                // One tap of the 16-channel window is a 32 x 16 matrix with a single non-zero per row, so two taps side
+                // by side (K = 32) satisfy the 2:4 pattern of the sparse MFMA, which multiplies them in the time of one
+                // dense tap.  Tap 0 goes first, as a dense MFMA that starts the accumulation from zero; taps (1,2),
+                // (3,4), (5,6), (7,8) follow as four sparse ones: the lower half of the lanes carries the first tap of
+                // a pair in its eight compressed A slots, the upper half the second (the record packs them so), and B
+                // is the two taps' 16-byte LDS reads side by side.
+                // The row's column cw of the window lies in compressed slot 2 (cw / 4) + (cw % 4 == 3), with index
+                // code cw % 4; the other slot of each pair is zero under a code that keeps the pair ordered (even
+                // slot 0, odd slot 3).  For the dense tap the lane holds columns 8 lhi .. 8 lhi + 7 as they are.
+                const uint32_t cw = (rb[0] >> 16) & 15u;
+                const uint32_t pr = cw >> 2, code = cw & 3u;
+                const uint32_t hm = code == 3u ? 0xFFFF0000u : 0x0000FFFFu;
+                const int sidx = (int)(0xCCCCu | ((code == 3u ? 0u : code) << (4u * pr)));
+                const int rel = (int)cw - 8 * lhi;
+                const uint32_t hd = (rel & 1) ? 0xFFFF0000u : 0x0000FFFFu;
+                uint32_t m[4], md[4];
 #pragma unroll
-                for (int u = 0; u < 3; ++u) {
-                    const int q = 2 * NPB * u;
-#pragma unroll
-                    for (int side = 0; side < 2; ++side) {
-                        const u32x4_t a = a_operand(3 * u + 2 * side);
-#pragma unroll
-                        for (int pb = 0; pb < NPB; ++pb)
-                            t[pb] = Op::mfma(a, bq[(q + NPB * side + pb) % kDepth], (u == 0 && side == 0) ? zero : t[pb]);
+                for (int d = 0; d < 4; ++d) {
+                    m[d] = pr == (uint32_t)d ? hm : 0u;
+                    md[d] = (rel >> 1) == d ? hd : 0u;
+                }
+                auto pair_a = [&](int i) {
+                    const uint32_t dup = __builtin_amdgcn_perm(ra[i], ra[i], psel);
+                    return u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
+                };
+                auto slot = [](int r, int pb) { return (NPB * r + pb) % kDepth; };
+                // read r of block pb has been consumed: the read kDepth further on takes its queue slot
+                auto refill = [&](int r, int pb) {
+                    const int i = NPB * r + pb, n = i + kDepth;
+                    if (n < kReads) {
+                        bq[i % kDepth] = read16(src[n % NPB] + tap_offset(read_tap(n / NPB)));
+                    } else {  // (read in vain when the next row block does not chain)
+                        bq[i % kDepth] = read16(src[n % NPB] + next_delta + tap_offset(read_tap((n - kReads) / NPB)));
                     }
-                    const u32x4_t a = a_operand(3 * u + 1);
-#pragma unroll
-                    for (int pb = 0; pb < NPB; ++pb) {
-                        u32x4_t &bl = bq[(q + pb) % kDepth], &br = bq[(q + NPB + pb) % kDepth];
+                };
+                const uint32_t dup0 = __builtin_amdgcn_perm(rb[0], rb[0], 0x01000100u);
+                const u32x4_t a_first = u32x4_t{dup0 & md[0], dup0 & md[1], dup0 & md[2], dup0 & md[3]};
+                if constexpr (kShare) {
+                    // Stride 1: the middle tap of a filter row is not read from LDS.  Its operand is, lane by lane, the
+                    // left tap's operand of the next pixel or the right tap's of the previous one, both in registers of
+                    // neighbouring lanes of the same 16-lane row: two DPP moves per dword (lanes 0-3 and 8-11 of a row
+                    // take the former, lanes 4-7 and 12-15 the latter, so no lane reaches across a tile row's end).
+                    // Reads in order: left and right tap of filter row 0, of row 1, of row 2 (each for all blocks).
+                    auto middle = [&](const u32x4_t &bl, const u32x4_t &br) {
                         u32x4_t mid;
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
@@ -476,32 +518,61 @@ void gdws_fused_kernel(FusedParams params)
                                 mid[d] = (lane & 2) ? pv : nx;
                             }
                         }
-                        t[pb] = Op::mfma(a, mid, t[pb]);
+                        return mid;
+                    };
+                    {   // tap 0 alone, then taps (1, 2): middle and right of filter row 0
+                        const u32x4_t a = pair_a(0);
 #pragma unroll
-                        for (int side = 0; side < 2; ++side) {
-                            const int i = q + NPB * side + pb, n = i + kDepth;  // read n takes the slot that read i frees
-                            if (n < kReads) {
-                                bq[i % kDepth] = read16(src[n % NPB] + tap_offset(read_tap(n / NPB)));
-                            } else {  // (read in vain, from the stage's first window, when the next row block does not chain)
-                                bq[i % kDepth] =
-                                    read16(src[n % NPB] + next_delta + tap_offset(read_tap((n - kReads) / NPB)));
-                            }
+                        for (int pb = 0; pb < NPB; ++pb) t[pb] = Op::mfma(a_first, bq[slot(0, pb)], zero);
+#pragma unroll
+                        for (int pb = 0; pb < NPB; ++pb) {
+                            const u32x4_t mid = middle(bq[slot(0, pb)], bq[slot(1, pb)]);
+                            t[pb] = Op::smfmac(a, mid, bq[slot(1, pb)], t[pb], sidx);
+                            refill(0, pb);
+                            refill(1, pb);
                         }
                     }
-                }
-            } else {
+                    {   // taps (3, 4): left and middle of filter row 1
+                        const u32x4_t a = pair_a(1);
 #pragma unroll
-                for (int tap = 0; tap < 9; ++tap) {
-                    const u32x4_t a = a_operand(tap);
+                        for (int pb = 0; pb < NPB; ++pb) {
+                            const u32x4_t mid = middle(bq[slot(2, pb)], bq[slot(3, pb)]);
+                            t[pb] = Op::smfmac(a, bq[slot(2, pb)], mid, t[pb], sidx);
+                            refill(2, pb);
+                        }
+                    }
+                    {   // taps (5, 6): right of filter row 1, left of row 2
+                        const u32x4_t a = pair_a(2);
+#pragma unroll
+                        for (int pb = 0; pb < NPB; ++pb) {
+                            t[pb] = Op::smfmac(a, bq[slot(3, pb)], bq[slot(4, pb)], t[pb], sidx);
+                            refill(3, pb);
+                        }
+                    }
+                    {   // taps (7, 8): middle and right of filter row 2
+                        const u32x4_t a = pair_a(3);
+#pragma unroll
+                        for (int pb = 0; pb < NPB; ++pb) {
+                            const u32x4_t mid = middle(bq[slot(4, pb)], bq[slot(5, pb)]);
+                            t[pb] = Op::smfmac(a, mid, bq[slot(5, pb)], t[pb], sidx);
+                            refill(4, pb);
+                            refill(5, pb);
+                        }
+                    }
+                } else {
 #pragma unroll
                     for (int pb = 0; pb < NPB; ++pb) {
-                        const int i = NPB * tap + pb;  // position in the sequence of LDS reads
-                        t[pb] = Op::mfma(a, bq[i % kDepth], tap == 0 ? zero : t[pb]);
-                        const int n = i + kDepth;      // the read that takes the freed queue slot
-                        if (n < kReads) {
-                            bq[i % kDepth] = read16(src[n % NPB] + tap_offset(n / NPB));
-                        } else {  // (read in vain, from the stage's first window, when the next row block does not chain)
-                            bq[i % kDepth] = read16(src[n % NPB] + next_delta + tap_offset((n - kReads) / NPB));
+                        t[pb] = Op::mfma(a_first, bq[slot(0, pb)], zero);
+                        refill(0, pb);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const u32x4_t a = pair_a(i);
+#pragma unroll
+                        for (int pb = 0; pb < NPB; ++pb) {
+                            t[pb] = Op::smfmac(a, bq[slot(2 * i + 1, pb)], bq[slot(2 * i + 2, pb)], t[pb], sidx);
+                            refill(2 * i + 1, pb);
+                            refill(2 * i + 2, pb);
                         }
                     }
                 }

@@ -75,7 +75,9 @@ TileChoice choose_tile(int Ho, int Wo, int stride, int C, int mb, bool nhwc, boo
             const int npix = TN * IH * IW;
             const int nent = (npix + pstep - 1) / pstep;
             if (nhwc && nent > kMaxEnt) continue;
-            const int stage_w = (nhwc ? nent * pstep : npix) * (sg.stage_channels / 2 + 4);
+            // rows of IW pixels plus the row pad; the NHWC loader's last pass may run past the tile
+            const int in_rows = nhwc ? (nent * pstep + IW - 1) / IW : TN * IH;
+            const int stage_w = in_rows * (IW * lds_pixel_dwords(sg.stage_channels, stride) + lds_row_pad(TW, stride));
             // (depthwise-only mode: no output tile, but the waves' staging areas sit behind the input buffers)
             const size_t lds = gdw_only ? (size_t)sg.buffers * stage_w * 4 + (size_t)tile_px * 80
                                         : std::max((size_t)sg.buffers * stage_w * 4, out_bytes);
@@ -141,18 +143,21 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
     s.buffers = sg.buffers;
     s.m_blocks = (M + 31) / 32;
     s.mb_per_wg = deep_stage ? 8 : s.m_blocks >= 3 ? 4 : 2;
-    // One tap of a 16-channel window per depthwise MFMA, or two taps of an 8-channel window (see the kernel): the
-    // second takes 5 instead of 9 depthwise MFMAs per row block and pixel block and about two thirds of the vector
-    // instructions, but may need more row blocks.  Row-block costs in MFMA slots (the pointwise stage is 2 per
-    // 32 output channels; the vector instructions of a row block counted as 6 and 4 slots: measured on the 64- and
-    // 128-channel workgroups).
+    // Depthwise stage on a 16-channel window (taps paired on the sparse MFMA) or on an 8-channel window (two taps per
+    // dense MFMA, see the kernel): both take five matrix instructions per row block and pixel block; the second needs
+    // fewer vector instructions (no lane exchange for the middle taps) but, with few filters per channel, more row
+    // blocks.  Row-block costs in MFMA slots (the pointwise stage is 2 per 32 output channels; the vector
+    // instructions of a row block counted as 5.5 and 4 slots: measured on config 2's g = 9 layer, where both cut the
+    // layer into the same row blocks, and on the network shapes).
     s.tap2 = false;
     if (allow_tap2 && !gdw_only && !deep_stage && G > 0) {
         const int mbw = std::min(s.mb_per_wg, s.m_blocks);
-        const double c16 = 9 + 2 * mbw + 6, c8 = 5 + 2 * mbw + 4;
+        const double c16 = 5 + 2 * mbw + 5.5, c8 = 5 + 2 * mbw + 4;
         s.tap2 = count_row_blocks(C, sg.stage_channels, offsets, 8) * c8 < count_row_blocks(C, sg.stage_channels, offsets, kWindow) * c16;
     }
     const int window = s.tap2 ? 8 : kWindow;
+    // the general kernel's one-tap stage pairs taps on the sparse MFMA and reads its records in that form
+    s.sparse = !s.tap2 && !deep_stage;
     s.m_blocks_pad = (s.m_blocks + s.mb_per_wg - 1) / s.mb_per_wg * s.mb_per_wg;
     s.bias_pad.assign((size_t)s.m_blocks_pad * 32, 0.f);
     if (bias) std::copy(bias, bias + M, s.bias_pad.begin());
@@ -197,7 +202,7 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
                 rb.c0 = c0;
                 rb.stage = s.n_stages;
                 const int jf = std::min(jb, G - 1);  // a block of padding only takes the last window
-                rb.cb0 = std::min((chan[jf] / 4) * 4, cfill - kWindow);
+                rb.cb0 = std::min((chan[jf] / kWindowAlign) * kWindowAlign, cfill - kWindow);
                 int ng = 0;
                 while (ng < 4 && jb + 8 * (ng + 1) <= Gp) {
                     bool fits = true;
@@ -276,7 +281,10 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
         }
         uint32_t ctrl = (uint32_t)(rb.cb0 / 2) | ((uint32_t)(nwait & 15) << 8);
         if (new_stage) ctrl |= kCtrlNewStage;
-        if (chain) ctrl |= kCtrlChainNext | ((uint32_t)(rbs[k + 1].cb0 / 2) << 16);
+        if (chain) ctrl |= kCtrlChainNext;
+        // (the next window of the same stage is stored also without the chain bit: workgroups without loader waves
+        // have the whole stage in LDS and read ahead regardless)
+        if (k + 1 < rbs.size() && rbs[k + 1].stage == rb.stage) ctrl |= (uint32_t)(rbs[k + 1].cb0 / 2) << 16;
         for (int l = 0; l < 64; ++l) {
             const int jr = rb.rows[l & 31];
             uint32_t *qa = rec_a + (k * 64 + l) * 4, *qb = rec_b + (k * 64 + l) * 2;
@@ -284,13 +292,22 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
             if (jr >= 0) {
                 uint16_t h[9];
                 for (int t = 0; t < 9; ++t) h[t] = to_half_bits(dw[(size_t)jr * 9 + t], dtype);
-                for (int d = 0; d < 4; ++d) qa[d] = (uint32_t)h[2 * d] | ((uint32_t)h[2 * d + 1] << 16);
-                qb[0] = h[8];
-                // this lane holds columns 8*half .. 8*half+7 of its row; the row's only column is the channel
-                // (two-tap stage: both halves of the lanes hold the same 8 channels, each for its own tap)
-                const int pos = (chan[jr] - rb.c0 - rb.cb0) - (s.tap2 ? 0 : 8 * (l >> 5));
-                if (pos >= 0 && pos < 8) sel = (uint32_t)(pos / 2) | ((pos & 1) ? 8u : 0u);
+                if (s.sparse) {
+                    // tap 0 alone, then the pairs (1,2), (3,4), (5,6), (7,8); the select field is the row's column
+                    // of the window, the same in both halves of the lanes
+                    for (int d = 0; d < 4; ++d) qa[d] = (uint32_t)h[2 * d + 1] | ((uint32_t)h[2 * d + 2] << 16);
+                    qb[0] = h[0];
+                    sel = (uint32_t)(chan[jr] - rb.c0 - rb.cb0);
+                } else {
+                    for (int d = 0; d < 4; ++d) qa[d] = (uint32_t)h[2 * d] | ((uint32_t)h[2 * d + 1] << 16);
+                    qb[0] = h[8];
+                    // this lane holds columns 8*half .. 8*half+7 of its row; the row's only column is the channel
+                    // (two-tap stage: both halves of the lanes hold the same 8 channels, each for its own tap)
+                    const int pos = (chan[jr] - rb.c0 - rb.cb0) - (s.tap2 ? 0 : 8 * (l >> 5));
+                    if (pos >= 0 && pos < 8) sel = (uint32_t)(pos / 2) | ((pos & 1) ? 8u : 0u);
+                }
             }
+            if (s.sparse && jr < 0) sel = 0;  // (a row without a filter: all taps zero, any column)
             qb[0] |= (sel << 16) | (rb.own << 20);
             qb[1] = ctrl;
         }
