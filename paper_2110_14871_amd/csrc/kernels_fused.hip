@@ -185,29 +185,37 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
     };
     std::vector<RowBlock> rbs;
     int chunk_base = 0;  // chunks of the stages before the current one
-    for (int c0 = 0; c0 < C; c0 += s.stage_channels) {
-        const int cnt = std::min(s.stage_channels, C - c0);
-        const int cfill = (cnt + 15) & ~15;
-        int j = offsets[c0];
-        const int jend = offsets[c0 + cnt];
-        if (j == jend) continue;  // no filters on any channel of this stage: it is never loaded
-        if (gdw_only) {
-            // row blocks own whole groups of 8 consecutive intermediate channels (16-byte pieces of a row of T), up to
-            // the padded channel count; rows past G have no filter and produce the zero padding
-            const int Gp = (G + 15) & ~15;
-            if (c0 != 0 || cnt != C) { s.valid = false; return; }  // single-stage layers only
-            int jb = 0;
-            while (jb < Gp) {
+    if (gdw_only) {
+        // Row blocks own whole groups of 8 consecutive intermediate channels (16-byte pieces of a row of T), up to the
+        // padded channel count; rows past G have no filter and produce the zero padding.  A layer of several stages
+        // (stride 1) loads stages that overlap by 8 input channels, so that a group whose filters sit on at most 8
+        // consecutive input channels lies inside one stage; a group takes the first stage that holds it.
+        const int Gp = (G + 15) & ~15;
+        const bool multi = C > s.stage_channels;
+        if (multi && stride != 1) { s.valid = false; return; }
+        const int step = multi ? s.stage_channels - 8 : s.stage_channels;
+        int jb = 0;
+        for (int c0 = 0; c0 < C && jb < Gp; c0 += step) {
+            const int cnt = std::min(s.stage_channels, C - c0);
+            const int cfill = (cnt + 15) & ~15;
+            // the channels of group jb .. jb + 7 lie in [c0, c0 + cnt)
+            auto in_stage = [&](int j0) {
+                for (int q = j0; q < std::min(j0 + 8, G); ++q)
+                    if (chan[q] < c0 || chan[q] >= c0 + cnt) return false;
+                return true;
+            };
+            const size_t first_rb = rbs.size();
+            while (jb < Gp && (jb >= G || in_stage(jb))) {  // (padding follows the last group, in its stage)
                 RowBlock rb;
                 rb.c0 = c0;
                 rb.stage = s.n_stages;
                 const int jf = std::min(jb, G - 1);  // a block of padding only takes the last window
-                rb.cb0 = std::min((chan[jf] / kWindowAlign) * kWindowAlign, cfill - kWindow);
+                rb.cb0 = std::min(((chan[jf] - c0) / kWindowAlign) * kWindowAlign, cfill - kWindow);
                 int ng = 0;
                 while (ng < 4 && jb + 8 * (ng + 1) <= Gp) {
                     bool fits = true;
                     for (int q = jb + 8 * ng; q < std::min(jb + 8 * (ng + 1), G); ++q)
-                        fits = fits && chan[q] >= rb.cb0 && chan[q] - rb.cb0 < kWindow;
+                        fits = fits && chan[q] - c0 >= rb.cb0 && chan[q] - c0 - rb.cb0 < kWindow && chan[q] < c0 + cnt;
                     if (!fits) break;
                     ++ng;
                 }
@@ -218,8 +226,20 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
                 rbs.push_back(rb);
                 jb += 8 * ng;
             }
-            j = jend;
+            if (rbs.size() == first_rb) continue;  // no group lies in this stage: it is never loaded
+            s.stage_tab.push_back(c0);
+            s.stage_tab.push_back(cnt);
+            ++s.n_stages;
+            chunk_base += (cfill + s.chunk_channels - 1) / s.chunk_channels;
         }
+        if (jb < Gp) { s.valid = false; return; }  // a group spans more input channels than two stages share
+    }
+    for (int c0 = 0; c0 < C && !gdw_only; c0 += s.stage_channels) {
+        const int cnt = std::min(s.stage_channels, C - c0);
+        const int cfill = (cnt + 15) & ~15;
+        int j = offsets[c0];
+        const int jend = offsets[c0 + cnt];
+        if (j == jend) continue;  // no filters on any channel of this stage: it is never loaded
         while (j < jend) {
             RowBlock rb;
             rb.c0 = c0;
