@@ -156,6 +156,41 @@ def test_stages_separately(layout):
         assert rel_l2(from_device(y, dtype, layout), ref) <= (1e-6 if dtype == "f32" else 4e-3)
 
 
+@pytest.mark.parametrize("case", [
+    # C, N, H, W, rule: layers of several input stages (C > 128), whose depthwise stage alone runs on the matrix cores
+    # with stages that overlap by 8 channels
+    (256, 3, 8, 8, "u14"),
+    (136, 2, 10, 12, "u13"),        # a last stage of 24 channels, C no multiple of 16
+    (320, 2, 5, 7, "u09"),          # channels without filters: groups of 8 intermediate channels that reach further
+    (192, 1, 16, 16, "all9"),
+    (512, 2, 4, 4, "all1"),
+])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_depthwise_stage_alone_many_channels(case, dtype):
+    C, N, H, W, rule = case
+    g = _g(rule, C, 640 + C)
+    G, M = int(g.sum()), 16
+    x = rng.normal(510 + C, (N, C, H, W))
+    dw = rng.normal(511 + C, (G, 3, 3), std=0.3)
+    pw = rng.normal(512 + C, (M, G), std=0.1)
+    plan = gd.gdws_plan(gd.make_desc(C, M, 3, 1, 1, dtype, "nhwc"), g, dw=dw, pw=pw)
+    dwq, _ = gd.gdws_plan_factors(plan)
+    xd, x_exact = to_device(x, dtype, "nhwc")
+    Gt = gd.gdws_intermediate_channels(plan)
+    t = empty_act(N, Gt, H, W, dtype, "nhwc", fill=float("nan"))
+    gd.gdws_gdw_forward(plan, xd, t, N, H, W)
+    torch.cuda.synchronize()
+    th = from_device(t, dtype, "nhwc")
+    assert np.all(th[:, G:] == 0)
+    ref = oracle.gdw(x_exact, g, dwq, 1, 1)
+    th = th[:, :G]
+    assert rel_l2(th, ref) <= 4e-3
+    # every element: the fp32 sum of nine products, rounded once to the storage type
+    ulp = np.abs(ref) * 2.0 ** (-8 if dtype == "bf16" else -11)
+    slack = 9 * 2.0 ** -24 * oracle.gdw(np.abs(x_exact), g, np.abs(dwq), 1, 1) + (2.0 ** -133 if dtype == "bf16" else 2.0 ** -24)
+    assert np.all(np.abs(th - ref) <= ulp * (1 + 2.0 ** -6) + slack)
+
+
 # ------------------------------------------------------------------------------------------
 # shape sweep: several tiles, ragged tails, strides, kernel sizes, degenerate multipliers
 # ------------------------------------------------------------------------------------------
