@@ -38,6 +38,10 @@ constexpr int kWindow = 16;    // input channels one row block may draw from (K 
 // better than 64 cycles: those tiles keep 16 bytes of padding (aligned LDS writes).
 constexpr int lds_pixel_dwords(int stage_channels, int stride) { return stage_channels / 2 + (stride == 1 ? 2 : 4); }
 constexpr int lds_row_pad(int tw, int stride) { return stride == 1 && tw <= 8 ? 28 : 0; }
+// Behind everything else in LDS: the table of A-operand selectors of the sparse depthwise stage, 32 entries (window
+// column x lane half) of kLutEntry dwords.
+constexpr int kLutEntry = 12;
+constexpr int kLutBytes = 32 * kLutEntry * 4;
 
 // Record of a row block, per lane: six dwords in two arrays (16-byte and 8-byte loads).
 //   a[0..3]  taps 0..7 of the lane's row, two per dword

@@ -124,10 +124,12 @@ struct FusedParams {
     int th_log2;     // TH is a power of two
     int stage_w;     // dwords per LDS stage buffer
     uint32_t x_bytes;  // size of x (below 2 GiB): the bound of the loader's buffer descriptor
+    uint32_t y_bytes;  // depthwise-only mode: size of T (below 2 GiB), the bound of the stores' buffer descriptor
     int tiles_x, tiles_y;
     int c_begin0, c_count0;  // stage 0's entry of stage_tab
     int out_off;             // depthwise-only mode: dword offset in LDS of the waves' output staging areas
     int pool, Hp, Wp;        // pool != 0 (NHWC, no residual): y is the 2 x 2 / stride-2 max-pool of the output, Hp x Wp
+    int lut_off;             // dword offset in LDS of the table of A-operand selectors (kLutBytes, behind all else)
 };
 
 
@@ -197,8 +199,8 @@ void gdws_fused_kernel(FusedParams params)
 #define GDWS_PIN(f) asm volatile("" : "+s"(p.f))
     GDWS_PIN(n_stages); GDWS_PIN(n_rowblocks); GDWS_PIN(final_waits); GDWS_PIN(m_blocks_pad);
     GDWS_PIN(relu); GDWS_PIN(N); GDWS_PIN(C); GDWS_PIN(H); GDWS_PIN(W); GDWS_PIN(M); GDWS_PIN(Ho); GDWS_PIN(Wo);
-    GDWS_PIN(TH); GDWS_PIN(TN); GDWS_PIN(IH); GDWS_PIN(th_log2); GDWS_PIN(stage_w); GDWS_PIN(x_bytes); GDWS_PIN(tiles_x);
-    GDWS_PIN(tiles_y); GDWS_PIN(c_begin0); GDWS_PIN(c_count0); GDWS_PIN(out_off);
+    GDWS_PIN(TH); GDWS_PIN(TN); GDWS_PIN(IH); GDWS_PIN(th_log2); GDWS_PIN(stage_w); GDWS_PIN(x_bytes); GDWS_PIN(y_bytes); GDWS_PIN(tiles_x);
+    GDWS_PIN(tiles_y); GDWS_PIN(c_begin0); GDWS_PIN(c_count0); GDWS_PIN(out_off); GDWS_PIN(lut_off);
 #undef GDWS_PIN
     using Op = half_ops<DTYPE>;
     using Gm = Geom<TW, STRIDE, BIG>;
@@ -221,6 +223,33 @@ void gdws_fused_kernel(FusedParams params)
     float *tile32 = (float *)lds;
     int *pixtab = p.residual ? (int *)(tile32 + kRows * kRowFloats) : (int *)(tile16 + kRows * kRowHalfs);
 
+    // Sparse depthwise stage: how a lane places its tap in the A operand depends only on the row's window column cw
+    // (16 values) and on the lane's half, so the 32 cases are worked out once, by 32 threads, into a table in LDS that
+    // every row block reads with three loads (the compares and selects they replace are the slowest vector
+    // instructions of the loop).  An entry is nine dwords in twelve: byte selectors of v_perm_b32 that put the lane's
+    // tap of a record dword into A dword d of a pair of taps (0-3) and the first tap into A dword d of the dense
+    // MFMA (4-7) -- selector byte 0x0c yields zero -- and the index operand of the sparse MFMAs (8).
+    // The row's column cw lies in compressed slot 2 (cw / 4) + (cw % 4 == 3), with index code cw % 4; the other slot
+    // of each pair is zero under a code that keeps the pair ordered (even slot 0, odd slot 3).  For the dense tap a
+    // lane holds columns 8 lhi .. 8 lhi + 7 as they are.  (The first barrier every wave passes before its first row
+    // block orders these writes before the reads.)
+    if constexpr (!TAP2) {
+        if (threadIdx.x < 32) {
+            const uint32_t cw = threadIdx.x & 15u, lh = threadIdx.x >> 4;
+            const uint32_t pr = cw >> 2, code = cw & 3u;
+            const uint32_t tap = lh ? 0x0302u : 0x0100u;  // a record dword holds a pair's first tap below its second
+            const uint32_t sp = code == 3u ? (tap << 16 | 0x0C0Cu) : (0x0C0C0000u | tap);
+            const int rel = (int)cw - 8 * (int)lh;
+            const uint32_t sd = (rel & 1) ? 0x01000C0Cu : 0x0C0C0100u;
+            uint32_t *e = lds + p.lut_off + threadIdx.x * kLutEntry;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                e[d] = pr == (uint32_t)d ? sp : 0x0C0C0C0Cu;
+                e[4 + d] = (rel >> 1) == d ? sd : 0x0C0C0C0Cu;
+            }
+            e[8] = 0xCCCCu | ((code == 3u ? 0u : code) << (4u * pr));
+        }
+    }
     if (SELF || threadIdx.x >= kComputeThreads) {
         // ================================ loader waves ================================
         const int tid = SELF ? threadIdx.x : threadIdx.x - kComputeThreads;
@@ -364,13 +393,23 @@ void gdws_fused_kernel(FusedParams params)
         // (8 channels) of pixels l / 4 + 16 k.  The row blocks of this mode own whole groups of 8 intermediate channels.
         constexpr int kOutRow = 20;  // dwords per pixel in the staging area
         uint32_t *ostage = lds + p.out_off + wave * (32 * NPB * kOutRow);
-        int64_t opix[2 * NPB];       // element offset in T of the lane's pixels, -1: outside the image
+        // The stores go through a buffer descriptor, and a lane with nothing to store (a pixel outside the image, a
+        // quarter the row block does not own) gets an offset beyond the descriptor's bound, for which the hardware
+        // drops the store.  So every row block issues the same store instructions, without a branch around them, and
+        // the compiler's counts of outstanding memory operations stay exact: the wave waits for the records it
+        // loaded, not for the stores it issued after them (stores and loads share one in-order counter, and with
+        // conditional stores every wait for a load was also a wait for the previous row block's stores to land).
+        constexpr uint32_t kDropped = 0x80000000u;
+        uint32_t opix[2 * NPB];      // byte offset in T of the lane's piece of its pixels, kDropped: outside the image
+        const __amdgpu_buffer_rsrc_t yrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.y, 0, p.y_bytes, 0x00020000);
         if (GDWONLY) {
 #pragma unroll
             for (int k = 0; k < 2 * NPB; ++k) {
                 const int pp = wave * (32 * NPB) + (lane >> 2) + 16 * k, row = pp / TW;
                 const int ox = tx0 + (pp & (TW - 1)), oy = ty0 + (row & (p.TH - 1)), on = n0 + (row >> p.th_log2);
-                opix[k] = (on < p.N && oy < p.Ho && ox < p.Wo) ? (((int64_t)on * p.Ho + oy) * p.Wo + ox) * p.M : -1;
+                opix[k] = (on < p.N && oy < p.Ho && ox < p.Wo)
+                              ? (uint32_t)((on * p.Ho + oy) * p.Wo + ox) * (uint32_t)(p.M * 2) + (lane & 3) * 16
+                              : kDropped;
             }
         }
 
@@ -402,6 +441,16 @@ void gdws_fused_kernel(FusedParams params)
         // the byte selector that duplicates the lane's tap of a record dword (lower half of the lanes: the first tap
         // of the pair, upper half: the second)
         const uint32_t psel = lhi ? 0x03020302u : 0x01000100u;
+
+        // sparse depthwise stage: the current record's entry of the selector table
+        u32x4_t sp, sd;
+        int sidx = 0;
+        auto read_lut = [&]() {
+            const uint32_t *lut = lds + p.lut_off + (((rb[0] >> 16) & 15u) | (uint32_t)lhi << 4) * kLutEntry;
+            sp = *(const u32x4_t *)lut;
+            sd = *(const u32x4_t *)(lut + 4);
+            sidx = (int)lut[8];
+        };
 
         for (int idx = 0; idx < p.n_rowblocks; ++idx) {
             const uint32_t ctrl = (uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]);
@@ -464,24 +513,12 @@ void gdws_fused_kernel(FusedParams params)
                 // (3,4), (5,6), (7,8) follow as four sparse ones: the lower half of the lanes carries the first tap of
                 // a pair in its eight compressed A slots, the upper half the second (the record packs them so), and B
                 // is the two taps' 16-byte LDS reads side by side.
-                // The row's column cw of the window lies in compressed slot 2 (cw / 4) + (cw % 4 == 3), with index
-                // code cw % 4; the other slot of each pair is zero under a code that keeps the pair ordered (even
-                // slot 0, odd slot 3).  For the dense tap the lane holds columns 8 lhi .. 8 lhi + 7 as they are.
-                const uint32_t cw = (rb[0] >> 16) & 15u;
-                const uint32_t pr = cw >> 2, code = cw & 3u;
-                const uint32_t hm = code == 3u ? 0xFFFF0000u : 0x0000FFFFu;
-                const int sidx = (int)(0xCCCCu | ((code == 3u ? 0u : code) << (4u * pr)));
-                const int rel = (int)cw - 8 * lhi;
-                const uint32_t hd = (rel & 1) ? 0xFFFF0000u : 0x0000FFFFu;
-                uint32_t m[4], md[4];
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    m[d] = pr == (uint32_t)d ? hm : 0u;
-                    md[d] = (rel >> 1) == d ? hd : 0u;
-                }
+                // The byte selectors that place the lane's taps (sp, sd), and the index operand, come from the table in
+                // LDS: they were read when the record became the current one.
+                if (idx == 0) read_lut();
                 auto pair_a = [&](int i) {
-                    const uint32_t dup = __builtin_amdgcn_perm(ra[i], ra[i], psel);
-                    return u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
+                    return u32x4_t{__builtin_amdgcn_perm(ra[i], ra[i], sp[0]), __builtin_amdgcn_perm(ra[i], ra[i], sp[1]),
+                                   __builtin_amdgcn_perm(ra[i], ra[i], sp[2]), __builtin_amdgcn_perm(ra[i], ra[i], sp[3])};
                 };
                 auto slot = [](int r, int pb) { return (NPB * r + pb) % kDepth; };
                 // read r of block pb has been consumed: the read kDepth further on takes its queue slot
@@ -493,8 +530,8 @@ void gdws_fused_kernel(FusedParams params)
                         bq[i % kDepth] = read16(src[n % NPB] + next_delta + tap_offset(read_tap((n - kReads) / NPB)));
                     }
                 };
-                const uint32_t dup0 = __builtin_amdgcn_perm(rb[0], rb[0], 0x01000100u);
-                const u32x4_t a_first = u32x4_t{dup0 & md[0], dup0 & md[1], dup0 & md[2], dup0 & md[3]};
+                const u32x4_t a_first = u32x4_t{__builtin_amdgcn_perm(rb[0], rb[0], sd[0]), __builtin_amdgcn_perm(rb[0], rb[0], sd[1]),
+                                                __builtin_amdgcn_perm(rb[0], rb[0], sd[2]), __builtin_amdgcn_perm(rb[0], rb[0], sd[3])};
                 if constexpr (kShare) {
                     // Stride 1: the middle tap of a filter row is not read from LDS.  Its operand is, lane by lane, the
                     // left tap's operand of the next pixel or the right tap's of the previous one, both in registers of
@@ -592,6 +629,7 @@ void gdws_fused_kernel(FusedParams params)
                 rb = nb;
                 na = p.rec_a[ri];
                 nb = p.rec_b[ri];
+                if constexpr (!TAP2) read_lut();
             }
             if constexpr (GDWONLY) {
                 // ---- the block of T leaves: registers -> staging area -> global, 16 bytes per lane ----
@@ -606,12 +644,11 @@ void gdws_fused_kernel(FusedParams params)
                             *(u32x2_t *)(ostage + (pb * 32 + l32) * kOutRow + 8 * s2 + 4 * h + 2 * lhi) =
                                 u32x2_t{tb[pb][s2][2 * h], tb[pb][s2][2 * h + 1]};
                 const int quarter = lane & 3;
-                if (quarter < ng) {
+                const uint32_t gone = quarter < ng ? 0u : kDropped;
 #pragma unroll
-                    for (int k = 0; k < 2 * NPB; ++k) {
-                        const u32x4_t v = *(const u32x4_t *)(ostage + ((lane >> 2) + 16 * k) * kOutRow + quarter * 4);
-                        if (opix[k] >= 0) *(u32x4_t *)(p.y + opix[k] + jb + quarter * 8) = v;
-                    }
+                for (int k = 0; k < 2 * NPB; ++k) {
+                    const u32x4_t v = *(const u32x4_t *)(ostage + ((lane >> 2) + 16 * k) * kOutRow + quarter * 4);
+                    __builtin_amdgcn_raw_buffer_store_b128(v, yrsrc, (opix[k] + (uint32_t)jb * 2u) | gone, 0, 0);
                 }
             } else {
             // ---- pointwise ----

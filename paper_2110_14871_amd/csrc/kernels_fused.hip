@@ -79,8 +79,9 @@ TileChoice choose_tile(int Ho, int Wo, int stride, int C, int mb, bool nhwc, boo
             const int in_rows = nhwc ? (nent * pstep + IW - 1) / IW : TN * IH;
             const int stage_w = in_rows * (IW * lds_pixel_dwords(sg.stage_channels, stride) + lds_row_pad(TW, stride));
             // (depthwise-only mode: no output tile, but the waves' staging areas sit behind the input buffers)
-            const size_t lds = gdw_only ? (size_t)sg.buffers * stage_w * 4 + (size_t)tile_px * 80
-                                        : std::max((size_t)sg.buffers * stage_w * 4, out_bytes);
+            const size_t lds = ((gdw_only ? (size_t)sg.buffers * stage_w * 4 + (size_t)tile_px * 80
+                                          : std::max((size_t)sg.buffers * stage_w * 4, out_bytes)) + 15) / 16 * 16 +
+                               kLutBytes;
             if (lds > (size_t)kMaxLds) continue;
             const double cover = (double)((Wo + TW - 1) / TW * TW) * ((Ho + TH - 1) / TH * TH) / ((double)Wo * Ho);
             // halo rows/columns fetched per useful pixel; prefer fewer images per tile on ties
@@ -410,6 +411,9 @@ int launch_fused(const FusedArgs &a, hipStream_t s)
     if (a.pool && (!nhwc || sc.gdw_only || res || (a.M & 7) || tc.TH < 2)) return GDWS_EUNSUPPORTED;
     const int64_t x_bytes = (int64_t)a.N * a.C * a.H * a.W * 2;
     if (x_bytes >= ((int64_t)1 << 31) || (int64_t)a.N * a.H * a.W >= (1 << 24)) return GDWS_EUNSUPPORTED;
+    // (depthwise-only mode: T is stored through a buffer descriptor with 32-bit offsets)
+    const int64_t y_bytes = sc.gdw_only ? (int64_t)a.N * a.Ho * a.Wo * a.M * 2 : 0;
+    if (y_bytes >= ((int64_t)1 << 31)) return GDWS_EUNSUPPORTED;
     FusedParams p;
     p.x = (const uint16_t *)a.x; p.y = (uint16_t *)a.y;
     p.residual = (const uint16_t *)a.ep.residual; p.bias = sc.d_bias_pad;
@@ -421,10 +425,11 @@ int launch_fused(const FusedArgs &a, hipStream_t s)
     p.m_blocks_pad = sc.m_blocks_pad; p.relu = a.ep.relu;
     p.N = a.N; p.C = a.C; p.H = a.H; p.W = a.W; p.M = a.M; p.Ho = a.Ho; p.Wo = a.Wo;
     p.TH = tc.TH; p.TN = tc.TN; p.IH = tc.IH; p.th_log2 = tc.th_log2;
-    p.stage_w = tc.stage_w; p.x_bytes = (uint32_t)x_bytes;
+    p.stage_w = tc.stage_w; p.x_bytes = (uint32_t)x_bytes; p.y_bytes = (uint32_t)y_bytes;
     p.c_begin0 = sc.stage_tab[0]; p.c_count0 = sc.stage_tab[1];
     p.pool = a.pool; p.Hp = a.Ho / 2; p.Wp = a.Wo / 2;
     p.out_off = stage_geometry(a.stride, a.C).buffers * tc.stage_w;
+    p.lut_off = (int)((tc.lds_bytes - kLutBytes) / 4);
     p.tiles_x = (a.Wo + tc.TW - 1) / tc.TW;
     p.tiles_y = (a.Ho + tc.TH - 1) / tc.TH;
     const int tiles_n = (a.N + tc.TN - 1) / tc.TN;
