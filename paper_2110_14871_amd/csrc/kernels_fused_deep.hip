@@ -405,11 +405,26 @@ __global__ __launch_bounds__(256) void gdws_deep_finish_kernel(DeepFinishParams 
 #pragma unroll
     for (int k = 0; k < 8; ++k) v[k] = 0.f;
     if (live) {
-        for (int z = 0; z < p.slices; ++z) {
-            const float *src = p.part + z * p.part_slice + pix * p.mpad + mch;
-            const f32x4_t a = *(const f32x4_t *)src, b = *(const f32x4_t *)(src + 4);
+        // (the loads of eight slices go out together: one round trip to memory per batch instead of one per slice;
+        // the additions stay in slice order)
+        constexpr int kBatch = 8;
+        const float *src0 = p.part + pix * p.mpad + mch;
+        for (int z0 = 0; z0 < p.slices; z0 += kBatch) {
+            f32x4_t a[kBatch], b[kBatch];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) { v[k] += a[k]; v[4 + k] += b[k]; }
+            for (int j = 0; j < kBatch; ++j) {
+                const int z = z0 + j < p.slices ? z0 + j : z0;  // (past the last slice: read again, not added)
+                const float *src = src0 + z * p.part_slice;
+                a[j] = *(const f32x4_t *)src;
+                b[j] = *(const f32x4_t *)(src + 4);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (z0 + j < p.slices) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) { v[k] += a[j][k]; v[4 + k] += b[j][k]; }
+                }
+            }
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) v[k] += p.bias[mch + k];
