@@ -12,8 +12,8 @@
 // order, into "row blocks" of at most 32 whose input channels fit one 16-channel window.  For a
 // row block the depthwise stage is, per 32 pixels, one matrix instruction per filter tap or pair of taps: A
 // is the 32 x 16 matrix that holds tap (u,v) of intermediate channel j in column chan_of[j] (one non-zero per
-// row, built in registers from a per-lane tap value and a per-lane mask; two taps side by side are the 2:4
-// sparse operand of v_smfmac_f32_32x32x32), B is the 16-channel slice of
+// row, built in registers from a per-lane tap value by byte permutes whose selectors depend only on the row's window
+// column; two taps side by side are the 2:4 sparse operand of v_smfmac_f32_32x32x32), B is the 16-channel slice of
 // the input tile shifted by (u,v), read straight from LDS.  The 32 x 32 fp32 result is rounded to the
 // storage type in the lane that holds it and is, without any data movement, the B operand of the
 // pointwise MFMAs (the pointwise weights are packed at plan time in the matching K order).
