@@ -191,6 +191,42 @@ def test_depthwise_stage_alone_many_channels(case, dtype):
     assert np.all(np.abs(th - ref) <= ulp * (1 + 2.0 ** -6) + slack)
 
 
+@pytest.mark.parametrize("case", [
+    # C, N, H, W, rule: ragged images (tiles that hang over the edge), row blocks that own one to four groups of 8
+    # intermediate channels, images narrower than a tile row
+    (32, 3, 13, 11, "u13"),
+    (64, 2, 17, 5, "all1"),
+    (128, 2, 9, 19, "u09"),
+    (48, 5, 3, 3, "u14"),
+    (160, 2, 7, 9, "u13"),          # several input stages
+])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_depthwise_stage_alone_writes_only_its_output(case, dtype):
+    """The depthwise stage alone stores T through a bounds-checked descriptor, masked lanes carrying an offset outside
+    it: T is right on ragged shapes and the memory on either side of T keeps its contents."""
+    C, N, H, W, rule = case
+    g = _g(rule, C, 700 + C)
+    G, M = int(g.sum()), 16
+    x = rng.normal(520 + C, (N, C, H, W))
+    dw = rng.normal(521 + C, (G, 3, 3), std=0.3)
+    pw = rng.normal(522 + C, (M, G), std=0.1)
+    plan = gd.gdws_plan(gd.make_desc(C, M, 3, 1, 1, dtype, "nhwc"), g, dw=dw, pw=pw)
+    dwq, _ = gd.gdws_plan_factors(plan)
+    xd, x_exact = to_device(x, dtype, "nhwc")
+    Gt = gd.gdws_intermediate_channels(plan)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float16
+    n, guard = N * H * W * Gt, 4096
+    buf = torch.full((n + 2 * guard,), 7.0, dtype=tdt, device="cuda")
+    t = buf[guard:guard + n].view(N, H, W, Gt)
+    t.fill_(float("nan"))
+    gd.gdws_gdw_forward(plan, xd, t, N, H, W)
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == 7.0).all()) and bool((buf[guard + n:] == 7.0).all())
+    th = from_device(t, dtype, "nhwc")
+    assert np.all(th[:, G:] == 0)
+    assert rel_l2(th[:, :G], oracle.gdw(x_exact, g, dwq, 1, 1)) <= 4e-3
+
+
 # ------------------------------------------------------------------------------------------
 # shape sweep: several tiles, ragged tails, strides, kernel sizes, degenerate multipliers
 # ------------------------------------------------------------------------------------------
