@@ -49,6 +49,7 @@ constexpr int kLutBytes = 32 * kLutEntry * 4;
 //                                   bits 0-9 first group of 8 intermediate channels the row block owns, bits 10-11
 //                                   number of groups - 1)   select: bits 0-2 = which of the lane's four A dwords holds the row's
 //                                   only column (4: none of them), bit 3 = upper half of that dword
+//   (this is the form of the two-tap depthwise stage; for the one-tap stage see FusedSchedule::sparse)
 //   b[1]     control word, the same in all lanes (see kCtrl*)
 constexpr uint32_t kCtrlNewStage = 1u << 12;   // the row block is the first of a stage that uses the other buffer
 constexpr uint32_t kCtrlChainNext = 1u << 13;  // the next row block reads the same buffer and waits for no chunk
@@ -61,7 +62,8 @@ struct FusedSchedule {
                              // pointwise fragments; only for layers that are a single stage
     bool tap2 = false;       // depthwise stage with two taps of an 8-channel window per MFMA (else one tap of 16 channels)
     bool sparse = false;     // records in the form of the sparse-MFMA depthwise stage (one tap of 16 channels, taps
-                             // paired): a[i] = taps 2i+1, 2i+2; b[0] = tap 0 | window column of the row << 16 | own << 20
+                             // paired; general and deep-layer kernel): a[i] = taps 2i+1, 2i+2; b[0] = tap 0 | window
+                             // column of the row << 16 | own << 20
     int stride = 1;
     bool big = false;        // stage size class: stride 1: 128 (else 64) channels, stride 2: 32 (else 16)
     int stage_channels = 0;  // input channels per LDS stage

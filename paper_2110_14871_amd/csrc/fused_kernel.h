@@ -170,6 +170,31 @@ __device__ inline void load_chunk_nchw(const FusedParams &p, uint32_t *lds, int 
     }
 }
 
+// Sparse depthwise stage: how a lane places its tap in the A operand depends only on the row's window column cw
+// (16 values) and on the lane's half, so the 32 cases are worked out once per workgroup, by 32 threads, into a table in
+// LDS that every row block reads with three loads (the compares and selects they replace are the slowest vector
+// instructions of the loop).  An entry is nine dwords in twelve: byte selectors of v_perm_b32 that put the lane's
+// tap of a record dword into A dword d of a pair of taps (0-3) and the first tap into A dword d of the dense
+// MFMA (4-7) -- selector byte 0x0c yields zero -- and the index operand of the sparse MFMAs (8).
+// The row's column cw lies in compressed slot 2 (cw / 4) + (cw % 4 == 3), with index code cw % 4; the other slot
+// of each pair is zero under a code that keeps the pair ordered (even slot 0, odd slot 3).  For the dense tap a
+// lane holds columns 8 lh .. 8 lh + 7 as they are.  (A workgroup barrier must lie between these writes and the
+// first read: in the kernels here the first one every wave passes before its first row block.)
+__device__ inline void write_selector_entry(uint32_t *e, uint32_t cw, uint32_t lh)
+{
+    const uint32_t pr = cw >> 2, code = cw & 3u;
+    const uint32_t tap = lh ? 0x0302u : 0x0100u;  // a record dword holds a pair's first tap below its second
+    const uint32_t sp = code == 3u ? (tap << 16 | 0x0C0Cu) : (0x0C0C0000u | tap);
+    const int rel = (int)cw - 8 * (int)lh;
+    const uint32_t sd = (rel & 1) ? 0x01000C0Cu : 0x0C0C0100u;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        e[d] = pr == (uint32_t)d ? sp : 0x0C0C0C0Cu;
+        e[4 + d] = (rel >> 1) == d ? sd : 0x0C0C0C0Cu;
+    }
+    e[8] = 0xCCCCu | ((code == 3u ? 0u : code) << (4u * pr));
+}
+
 // NPB: 32-pixel blocks per compute wave.  2: a workgroup's tile is 256 output pixels.  1 (NHWC): 128 pixels, half the
 // MFMAs per row block and wave -- for layers with so few tiles that 256-pixel tiles leave the chip idle.
 // SELF (NHWC, layers whose input channels are one stage): no loader waves.  The workgroup is the four compute waves,
@@ -223,32 +248,8 @@ void gdws_fused_kernel(FusedParams params)
     float *tile32 = (float *)lds;
     int *pixtab = p.residual ? (int *)(tile32 + kRows * kRowFloats) : (int *)(tile16 + kRows * kRowHalfs);
 
-    // Sparse depthwise stage: how a lane places its tap in the A operand depends only on the row's window column cw
-    // (16 values) and on the lane's half, so the 32 cases are worked out once, by 32 threads, into a table in LDS that
-    // every row block reads with three loads (the compares and selects they replace are the slowest vector
-    // instructions of the loop).  An entry is nine dwords in twelve: byte selectors of v_perm_b32 that put the lane's
-    // tap of a record dword into A dword d of a pair of taps (0-3) and the first tap into A dword d of the dense
-    // MFMA (4-7) -- selector byte 0x0c yields zero -- and the index operand of the sparse MFMAs (8).
-    // The row's column cw lies in compressed slot 2 (cw / 4) + (cw % 4 == 3), with index code cw % 4; the other slot
-    // of each pair is zero under a code that keeps the pair ordered (even slot 0, odd slot 3).  For the dense tap a
-    // lane holds columns 8 lhi .. 8 lhi + 7 as they are.  (The first barrier every wave passes before its first row
-    // block orders these writes before the reads.)
     if constexpr (!TAP2) {
-        if (threadIdx.x < 32) {
-            const uint32_t cw = threadIdx.x & 15u, lh = threadIdx.x >> 4;
-            const uint32_t pr = cw >> 2, code = cw & 3u;
-            const uint32_t tap = lh ? 0x0302u : 0x0100u;  // a record dword holds a pair's first tap below its second
-            const uint32_t sp = code == 3u ? (tap << 16 | 0x0C0Cu) : (0x0C0C0000u | tap);
-            const int rel = (int)cw - 8 * (int)lh;
-            const uint32_t sd = (rel & 1) ? 0x01000C0Cu : 0x0C0C0100u;
-            uint32_t *e = lds + p.lut_off + threadIdx.x * kLutEntry;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                e[d] = pr == (uint32_t)d ? sp : 0x0C0C0C0Cu;
-                e[4 + d] = (rel >> 1) == d ? sd : 0x0C0C0C0Cu;
-            }
-            e[8] = 0xCCCCu | ((code == 3u ? 0u : code) << (4u * pr));
-        }
+        if (threadIdx.x < 32) write_selector_entry(lds + p.lut_off + threadIdx.x * kLutEntry, threadIdx.x & 15u, threadIdx.x >> 4);
     }
     if (SELF || threadIdx.x >= kComputeThreads) {
         // ================================ loader waves ================================

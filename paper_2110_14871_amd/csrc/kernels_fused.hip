@@ -157,8 +157,8 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
         s.tap2 = count_row_blocks(C, sg.stage_channels, offsets, 8) * c8 < count_row_blocks(C, sg.stage_channels, offsets, kWindow) * c16;
     }
     const int window = s.tap2 ? 8 : kWindow;
-    // the general kernel's one-tap stage pairs taps on the sparse MFMA and reads its records in that form
-    s.sparse = !s.tap2 && !deep_stage;
+    // the one-tap stage (general and deep-layer kernel) pairs taps on the sparse MFMA and reads its records in that form
+    s.sparse = !s.tap2;
     s.m_blocks_pad = (s.m_blocks + s.mb_per_wg - 1) / s.mb_per_wg * s.mb_per_wg;
     s.bias_pad.assign((size_t)s.m_blocks_pad * 32, 0.f);
     if (bias) std::copy(bias, bias + M, s.bias_pad.begin());
@@ -322,9 +322,9 @@ void build_fused_schedule(FusedSchedule &s, int dtype, int stride, int C, int M,
                 } else {
                     for (int d = 0; d < 4; ++d) qa[d] = (uint32_t)h[2 * d] | ((uint32_t)h[2 * d + 1] << 16);
                     qb[0] = h[8];
-                    // this lane holds columns 8*half .. 8*half+7 of its row; the row's only column is the channel
-                    // (two-tap stage: both halves of the lanes hold the same 8 channels, each for its own tap)
-                    const int pos = (chan[jr] - rb.c0 - rb.cb0) - (s.tap2 ? 0 : 8 * (l >> 5));
+                    // two-tap stage: both halves of the lanes hold the same 8 channels, each for its own tap; the
+                    // row's only column is the channel
+                    const int pos = chan[jr] - rb.c0 - rb.cb0;
                     if (pos >= 0 && pos < 8) sel = (uint32_t)(pos / 2) | ((pos & 1) ? 8u : 0u);
                 }
             }

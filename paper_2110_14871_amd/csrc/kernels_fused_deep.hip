@@ -5,13 +5,13 @@
 // a workgroup per CU, and every slice repeats the depthwise stage of the tile, which is most of a row block's
 // instructions.  Here the four waves of a workgroup share ONE block of 32 output pixels and split the output
 // channels instead (64 each, 256 per workgroup): the row blocks are taken four at a time, wave w computes the
-// depthwise stage of row block 4 k + w for the 32 pixels (nine MFMAs, as in the general kernel: sparse A from the
-// row block's record, B a 16-byte LDS read of the input tile, the middle tap of a filter row from the neighbouring
-// lanes), rounds the 32 x 32 result and puts it into LDS in the layout the pointwise MFMA wants for its B operand
+// depthwise stage of row block 4 k + w for the 32 pixels (one dense and four sparse MFMAs, as in the general kernel:
+// A from the row block's record, B a 16-byte LDS read of the input tile, the middle tap of a filter row from the
+// neighbouring lanes), rounds the 32 x 32 result and puts it into LDS in the layout the pointwise MFMA wants for its B operand
 // (16 bytes per lane and K-step: conflict-free to write and to read); after a barrier every wave runs the
 // pointwise MFMAs of all four row blocks against its own 64 output channels.  The depthwise work of a tile is thus
-// done once per 256 output channels, and a wave issues 25 MFMAs per group of four row blocks where the general
-// kernel's 64-channel slices issue 52.
+// done once per 256 output channels, and a wave issues 21 MFMAs per group of four row blocks where the general
+// kernel's 64-channel slices issue 36.
 //
 // The whole input tile (32 pixels with halo, all C channels, pixel-major, 16 bytes of padding per pixel) is loaded
 // into LDS by the four waves before the first row block: one stage, no loader waves.  Records, pointwise
@@ -55,6 +55,7 @@ struct DeepParams {
     uint32_t x_bytes;
     int tiles_x, tiles_y;
     int tslot_off;  // dword offset in LDS of the intermediate's slots (behind the input tile)
+    int lut_off;    // dword offset in LDS of the table of A-operand selectors (behind the slots)
     int pool, Hp, Wp;
     // SPLIT: groups per workgroup, per-group channel ranges (lo | hi << 16), the partial sums [slice][pixel][channel]
     int groups_per_slice;
@@ -102,6 +103,8 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
             for (int mb = 0; mb < kDeepMbWave; ++mb) pwf[s][s2][mb] = fp[(s * 2 + s2) * kstep_stride + mb * 64];
 
     // ---- the input tile: 16-byte pieces, consecutive threads along a pixel's channels ----
+    // the table of A-operand selectors of the sparse depthwise stage (the barrier behind the tile's load orders it)
+    if (threadIdx.x < 32) write_selector_entry(lds + p.lut_off + threadIdx.x * kLutEntry, threadIdx.x & 15u, threadIdx.x >> 4);
     constexpr uint32_t kOutside = 0x80000000u;  // beyond the descriptor's bound: the load returns zeros
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.x_bytes, 0x00020000);
     if constexpr (SPLIT) {
@@ -205,25 +208,26 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
         for (int i = 0; i < 6; ++i) bq[i] = read16(src + tap_offset(3 * (i / 2) + 2 * (i % 2)));
     };
     read_operands((uint32_t)__builtin_amdgcn_readfirstlane((int)rb[1]));
+    // the current record's entry of the selector table: byte selectors for a pair of taps (sp) and for the first tap
+    // (sd), and the index operand of the sparse MFMAs
+    u32x4_t sp, sd;
+    int sidx;
+    auto read_lut = [&]() {
+        const uint32_t *lut = lds + p.lut_off + (((rb[0] >> 16) & 15u) | (uint32_t)lhi << 4) * kLutEntry;
+        sp = *(const u32x4_t *)lut;
+        sd = *(const u32x4_t *)(lut + 4);
+        sidx = (int)lut[8];
+    };
+    read_lut();
 
     for (int gi = g_begin; gi < g_end; ++gi) {
-        // ---- depthwise stage of row block 4 gi + wave ----
-        const uint32_t sel = rb[0] >> 16;
-        const uint32_t hm = (sel & 8) ? 0xFFFF0000u : 0x0000FFFFu;
-        uint32_t m[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) m[d] = (sel & 7) == (uint32_t)d ? hm : 0u;
-        auto a_operand = [&](int tap) {
-            const uint32_t word = tap == 8 ? rb[0] : ra[tap / 2];
-            const uint32_t dup = __builtin_amdgcn_perm(word, word, (tap & 1) ? 0x03020302u : 0x01000100u);
-            return u32x4_t{dup & m[0], dup & m[1], dup & m[2], dup & m[3]};
+        // ---- depthwise stage of row block 4 gi + wave: tap 0 as a dense MFMA that starts from zero, then the pairs
+        // (1,2), (3,4), (5,6), (7,8) on the sparse MFMA, as in the general kernel ----
+        auto pair_a = [&](int i) {
+            return u32x4_t{__builtin_amdgcn_perm(ra[i], ra[i], sp[0]), __builtin_amdgcn_perm(ra[i], ra[i], sp[1]),
+                           __builtin_amdgcn_perm(ra[i], ra[i], sp[2]), __builtin_amdgcn_perm(ra[i], ra[i], sp[3])};
         };
-        // two accumulation chains (the middle taps apart) so that consecutive MFMAs do not wait for each other
-        f32x16_t t = zero, tm = zero;
-#pragma unroll
-        for (int u = 0; u < 3; ++u) {
-            const u32x4_t &bl = bq[2 * u], &br = bq[2 * u + 1];
-            t = Op::mfma(a_operand(3 * u), bl, t);
+        auto middle = [&](const u32x4_t &bl, const u32x4_t &br) {
             u32x4_t mid;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -239,9 +243,15 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
                     mid[d] = (lane & 2) ? pv : nx;
                 }
             }
-            tm = Op::mfma(a_operand(3 * u + 1), mid, tm);
-            t = Op::mfma(a_operand(3 * u + 2), br, t);
-        }
+            return mid;
+        };
+        const u32x4_t a_first = u32x4_t{__builtin_amdgcn_perm(rb[0], rb[0], sd[0]), __builtin_amdgcn_perm(rb[0], rb[0], sd[1]),
+                                        __builtin_amdgcn_perm(rb[0], rb[0], sd[2]), __builtin_amdgcn_perm(rb[0], rb[0], sd[3])};
+        f32x16_t t = Op::mfma(a_first, bq[0], zero);
+        t = Op::smfmac(pair_a(0), middle(bq[0], bq[1]), bq[1], t, sidx);
+        t = Op::smfmac(pair_a(1), bq[2], middle(bq[2], bq[3]), t, sidx);
+        t = Op::smfmac(pair_a(2), bq[3], bq[4], t, sidx);
+        t = Op::smfmac(pair_a(3), middle(bq[4], bq[5]), bq[5], t, sidx);
         // rounded to the storage type; register i of a lane is K element i % 8 of K-step i / 8 of the pointwise MFMA
         uint32_t *slot = tslots + ((gi & 1) * 4 + wave) * (2 * 64 * 4) + lane * 4;
 #pragma unroll
@@ -249,7 +259,7 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
             u32x4_t tb;
 #pragma unroll
             for (int d = 0; d < 4; ++d)
-                tb[d] = Op::pack(t[8 * s2 + 2 * d] + tm[8 * s2 + 2 * d], t[8 * s2 + 2 * d + 1] + tm[8 * s2 + 2 * d + 1]);
+                tb[d] = Op::pack(t[8 * s2 + 2 * d], t[8 * s2 + 2 * d + 1]);
             *(u32x4_t *)(slot + s2 * (64 * 4)) = tb;
         }
         // the next group's record becomes the current one; the one after it is requested
@@ -257,6 +267,7 @@ __global__ __launch_bounds__(kDeepThreads, 1) void gdws_deep_kernel(DeepParams p
             const uint32_t ri = (uint32_t)((gi + 2) * 4 + wave) * 64u + (uint32_t)lane;
             ra = na; rb = nb;
             na = p.rec_a[ri]; nb = p.rec_b[ri];
+            read_lut();
         }
         __syncthreads();  // the four row blocks of the group are in LDS
         // the next group's operands are requested now: they arrive during the pointwise MFMAs
@@ -490,7 +501,7 @@ DeepTile choose_deep_tile(int Ho, int Wo, int C, bool pool)
             const size_t npix = (size_t)TN * (TH + 2) * (TW + 2);
             const size_t in_bytes = npix * (cs / 2 + 4) * 4;
             const size_t out_bytes = (size_t)kDeepPx * (kDeepMbWg * 32 + 8) * 2 + kDeepPx * 4;
-            const size_t lds = std::max(in_bytes + (size_t)kTSlotDwords * 4, out_bytes);
+            const size_t lds = std::max(in_bytes + (size_t)kTSlotDwords * 4 + kLutBytes, out_bytes);
             if (lds > (size_t)kDeepMaxLds) continue;
             const double cover = (double)((Wo + TW - 1) / TW * TW) * ((Ho + TH - 1) / TH * TH) / ((double)Wo * Ho);
             const double halo = (double)(TH + 2) * (TW + 2) / (TH * TW);
@@ -563,6 +574,7 @@ int launch_fused_deep(const FusedArgs &a, void *workspace, size_t workspace_byte
     p.tiles_x = (a.Wo + t.TW - 1) / t.TW;
     p.tiles_y = (a.Ho + t.TH - 1) / t.TH;
     p.tslot_off = t.TN * (t.TH + 2) * (t.TW + 2) * (t.cs / 2 + 4);
+    p.lut_off = p.tslot_off + kTSlotDwords;
     p.pool = a.pool; p.Hp = a.Ho / 2; p.Wp = a.Wo / 2;
     p.groups_per_slice = p.n_groups; p.group_chan = sc.d_group_chan; p.part = nullptr; p.part_slice = 0;
     const int tiles_n = (a.N + t.TN - 1) / t.TN;
