@@ -230,13 +230,15 @@ bool fused_supported(const gdws_plan_t *p, int N, int H, int W)
 }
 
 constexpr int64_t kDeepMinWorkgroups = 64;
-constexpr int64_t kDeepMaxPixels = 6400;   // output pixels of the batch above which the general kernel's tiles fill the chip
-                                           // (measured: 4,096 and 6,272 pixels gain 10 to 30 %, 8,192 and 16,384 are even)
+// Output pixels of the batch above which the general kernel's tiles fill the chip and it is the faster one
+// (measured on the network shapes: 512 channels: 4,096 and 6,272 pixels gain 10 to 30 %, 8,192 lose 2 %; 256
+// channels: 16,384 pixels still gain).
+inline int64_t deep_max_pixels(int C) { return C <= 256 ? 16384 : 6400; }
 
 // Workspace with which the fused path splits a small launch of a deep layer (0: no such split for this call).
 size_t fused_split_bytes(const gdws_plan_t *p, int N, int H, int W, int Ho, int Wo, bool pool)
 {
-    if (!p->deep.valid || (int64_t)N * Ho * Wo > kDeepMaxPixels) return 0;
+    if (!p->deep.valid || (int64_t)N * Ho * Wo > deep_max_pixels(p->desc.C)) return 0;
     return deep_split_workspace_bytes(p->deep, N, p->desc.C, H, W, p->desc.M, Ho, Wo, pool);
 }
 
@@ -252,7 +254,7 @@ int run_fused(const gdws_plan_t *p, const void *x, const void *residual, void *y
     // grid gives the chip enough workgroups -- or, for the smallest launches, when the caller's workspace lets it
     // split the row blocks over workgroups as well.
     const int64_t dwg = deep_workgroups(p->deep, N, a.C, H, W, a.M, Ho, Wo, pool != 0);
-    if (dwg > 0 && (int64_t)N * Ho * Wo <= kDeepMaxPixels && !(pool && a.ep.residual)) {
+    if (dwg > 0 && (int64_t)N * Ho * Wo <= deep_max_pixels(a.C) && !(pool && a.ep.residual)) {
         const size_t split = fused_split_bytes(p, N, H, W, Ho, Wo, pool != 0);
         const bool can_split = split > 0 && ws && ws_bytes >= split;
         if (dwg >= kDeepMinWorkgroups || can_split) {
